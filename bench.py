@@ -1,0 +1,153 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE-layer hot path on one MI355X.
+
+A step is one call of the fused layer (router, permutation, grouped SwiGLU expert
+FFN over paged weights, combine) on one micro-batch of synthetic input that is
+already resident in HBM.  Default workload: the Mixtral-8x7B-shaped layer with
+4096 tokens, the configuration the headline metric is quoted on.
+
+Prints ONE JSON line: tokens/s of the whole layer, the roofline of the dominant
+kernel (the gate/up expert GEMM, measured with HIP events recorded by the
+library on the launch stream while the timed steps run again) and the CPU oracle
+timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak, TFLOP/s
+PEAK_HBM_GBS = 8000.0
+
+# HBM traffic per launch of the gate/up GEMM on the default workload, in bytes, from the
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/ (None: not measured).
+MEASURED_TRAFFIC = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c3_mixtral8x7b_t4096")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=192)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--option", action="append", default=[], help="library option name=value")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2411_11217_amd as M
+    from moe_workloads import CONFIGS, make_inputs, oracle_view
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    cfg = CONFIGS[args.config]
+    for o in args.option:
+        name, val = o.split("=")
+        M.set_option(name, int(val))
+    s = M.make_shape(cfg.T, cfg.H, cfg.F, cfg.E, cfg.k, cfg.dtype, cfg.page_bytes)
+    t0 = time.time()
+    inp = make_inputs(cfg, threads=16)
+    pw = M.PagedWeights(s, inp["W1"], inp["W3"], inp["W2"], pin=cfg.streamed)
+    x, Wr = inp["x"].cuda(), inp["Wr"].cuda()
+    bias = None if inp["bias"] is None else inp["bias"].cuda()
+    streamer = None
+    if cfg.streamed:
+        streamer = M.Streamer(s, pw.pages_host, pw.table_host)
+    else:
+        pw.to_device(keep_host=False)
+    ws = M.Workspace(s)
+    y = torch.empty((cfg.T, cfg.H), dtype=torch.float32, device="cuda")
+    print(f"[bench] inputs ready in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+
+    def step():
+        if streamer is not None:
+            M.moe_layer_streamed(streamer, x, Wr, bias=bias, workspace=ws, y=y)
+        else:
+            M.moe_layer(s, x, Wr, pw.table_dev, pw.pages_dev, bias=bias, workspace=ws, y=y)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    tokens_per_s = cfg.T / (ms_per_step * 1e-3)
+
+    # the same steps again with the library's stage events on (HIP events on the launch stream)
+    stages, n_prof = {}, 0
+    if streamer is None:
+        M.set_option("profile", 1)
+        for _ in range(min(args.steps, 200)):
+            step()
+        torch.cuda.synchronize()
+        stages, n_prof = M.profile_read()
+        M.set_option("profile", 0)
+    flops_gu = 4.0 * cfg.R * cfg.H * cfg.F            # gate/up GEMM: 2 * R * H * 2F
+    flops_ffn = cfg.ffn_flops
+    roofline = None
+    if stages:
+        t_gu = stages["gemm_gate_up"] * 1e-3
+        achieved = flops_gu / t_gu / 1e12
+        roofline = {"bound": "mfma", "kernel": "ffn_gemm_bf16<0> (gate/up expert GEMM + SwiGLU epilogue)",
+                    "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get(args.config),
+                    "avg_launch_ms": round(stages["gemm_gate_up"], 4), "launches_timed": n_prof}
+    extra = {}
+    if stages:
+        t_ffn = (stages["gemm_gate_up"] + stages["gemm_down"]) * 1e-3
+        extra = {
+            "stage_ms": {k: round(v, 4) for k, v in stages.items()},
+            "expert_gemms_tflops": round(flops_ffn / t_ffn / 1e12, 2),
+            "expert_gemms_frac_of_bf16_peak": round(flops_ffn / t_ffn / 1e12 / PEAK_BF16_TFLOPS, 4),
+            "layer_tflops": round((flops_ffn + cfg.router_flops) / (ms_per_step * 1e-3) / 1e12, 2),
+        }
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        n = min(args.cpu_sample_tokens, cfg.T)
+        v = {k: oracle_view(t) for k, t in inp.items() if k != "bias"}
+        b = None if inp["bias"] is None else inp["bias"].numpy().astype(np.float64)
+        xs = np.ascontiguousarray(v["x"][:n])
+        t0 = time.perf_counter()
+        ref = oracle.layer(xs, v["Wr"], v["W1"], v["W3"], v["W2"], cfg.k, cfg.dtype_code, bias=b)
+        dt = time.perf_counter() - t0
+        cpu_baseline = {"value": round(n / dt, 3), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+                        "sample": f"first {n} tokens of the workload, whole layer (route, permute, FFN, combine), {dt:.1f}s"}
+        # the sample doubles as a sanity check of the timed output
+        got = y[:n].cpu().numpy()
+        same = (np.sort(ws.view("topk_ids")[:n].cpu().numpy(), axis=1) == np.sort(ref["ids"], axis=1)).all(axis=1)
+        err = float(np.abs(got[same] - ref["y"][same]).max())
+        extra["max_abs_err_vs_oracle_on_sample"] = round(err, 6)
+
+    out = {
+        "metric": "MoE layer tokens/s + % bf16 MFMA peak (Mixtral-8x7B shape, 4096 tokens)",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "T": cfg.T, "H": cfg.H, "F": cfg.F, "E": cfg.E, "k": cfg.k,
+                   "page_bytes": cfg.page_bytes, "weights": "pinned host, streamed" if cfg.streamed else "resident in HBM"},
+        "roofline": roofline, "cpu_baseline": cpu_baseline,
+    }
+    out.update(extra)
+    print(json.dumps(out), flush=True)
+    if streamer is not None:
+        streamer.close()
+
+
+if __name__ == "__main__":
+    main()

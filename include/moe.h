@@ -1,0 +1,216 @@
+/*
+ * moe.h -- C ABI of the MI355X (gfx950) MoE-layer library.
+ *
+ * One call of the layer is what the paper's pipeline runs once per micro-batch
+ * inside its post-attention task (section 4.1: "O projection and MoE FFN"):
+ * a gating function picks k of the n_e expert feed-forward networks for every
+ * token and only those run (section 2.1).  Shape symbols follow the paper's
+ * notation table (section 4.2): h1 (here H) model hidden size, h2 (F) expert
+ * intermediate size, n_e (E) experts, k, dt (dtype); T is the micro-batch mu
+ * of section 3.3.  Expert weights are not dense arrays but fixed-size PAGES
+ * found through a PAGE TABLE, as in the paper's memory management (appendix
+ * A.1: weights move in pages, the MoE FFN kernel reaches them via a page
+ * table; a buffer of twice the streamed weights allows prefetch).
+ *
+ * General rules
+ *  - Plain C types only.  "device" pointers are HIP device memory, "host"
+ *    pointers ordinary host memory, "pinned" host memory from hipHostMalloc.
+ *  - The caller owns every buffer and every stream.  Hot calls enqueue work on
+ *    `stream` (a hipStream_t passed as void*; NULL = the default stream) and
+ *    return without waiting for it.  They never allocate or free memory.
+ *  - Every function returns MOE_OK (0) or a negative moe_status.  Arguments
+ *    are checked on the host before anything is enqueued; on error nothing was
+ *    enqueued.  T == 0 is valid and does nothing.
+ *  - All arrays are contiguous row-major.  R = T*k is the number of routed rows.
+ *  - dtype is the storage type of x, the router, the expert weights and the
+ *    intermediate h; logits, gate weights, expert outputs and y are float.
+ *
+ * Supported shapes: 1 <= k <= E <= MOE_MAX_EXPERTS, H and F multiples of 128,
+ * page_bytes a positive multiple of the weight-tile size (moe_tile_bytes).
+ */
+#ifndef MOE_H_
+#define MOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_MAX_EXPERTS 64
+
+typedef enum moe_status {
+    MOE_OK = 0,
+    MOE_ERR_INVALID_ARG = -1,        /* null pointer, bad shape, bad alignment */
+    MOE_ERR_UNSUPPORTED_DTYPE = -2,
+    MOE_ERR_WORKSPACE_TOO_SMALL = -3,
+    MOE_ERR_PAGE_NOT_RESIDENT = -4,  /* a needed page-table entry is -1 or outside the pool */
+    MOE_ERR_HIP = -5                 /* a HIP call failed; see moe_last_hip_error() */
+} moe_status;
+
+enum { MOE_DTYPE_F32 = 0, MOE_DTYPE_BF16 = 1 };
+
+typedef struct moe_shape {
+    int32_t T;          /* tokens in the micro-batch (mu) */
+    int32_t H;          /* h1 */
+    int32_t F;          /* h2 */
+    int32_t E;          /* n_e */
+    int32_t k;          /* experts per token */
+    int32_t dtype;      /* MOE_DTYPE_* */
+    int64_t page_bytes; /* size of one weight page */
+} moe_shape;
+
+const char* moe_status_string(int status);
+/* hipError_t value of the most recent failing HIP call on this thread (0 if none). */
+int moe_last_hip_error(void);
+/* MOE_OK if the shape is one the library supports. */
+int moe_validate_shape(const moe_shape* s);
+
+/* ------------------------------------------------------------------ paged weights
+ *
+ * Page format (this library's reading of the paper's weight pages, appendix
+ * A.1; the paper fixes neither page size nor content).  The unit is a TILE of
+ * 128 output features x 64 reduction elements (16 KiB bf16, 32 KiB f32), stored
+ * as 128 rows of 64 elements; inside a row the 16-byte chunk with index c is
+ * stored at chunk position c ^ (row & 7) for c < 8 (for f32 rows, which have 16
+ * chunks, bit 3 of c is kept), which is the bank-conflict-free image the GEMM
+ * kernels copy straight into LDS.  A page holds page_bytes / tile_bytes
+ * consecutive tiles and never spans experts.  Expert e owns
+ * pages_gu + pages_d logical pages:
+ *   group GU (logical pages 0 .. pages_gu-1): tiles ordered [f/128][w][h/64],
+ *       w = 0 for W1 (gate) rows f..f+127, w = 1 for W3 (up) rows f..f+127;
+ *   group D  (logical pages pages_gu .. ): tiles ordered [d/128][f/64] of W2.
+ * The last page of a group is zero padded.  page_table[e * pages_per_expert + p]
+ * is the slot of logical page p of expert e in the page pool (byte address
+ * pool + slot * page_bytes), or -1 if the page is not resident.
+ */
+int moe_tile_bytes(const moe_shape* s, int64_t* tile_bytes);
+int moe_pages_required(const moe_shape* s, int64_t* pages_gu, int64_t* pages_d);
+
+/* Host-side packer.  W1, W3: [E][F][H]; W2: [E][H][F] (host, dtype elements).
+ * page_table: host, [E][pages_gu+pages_d], every entry in [0, pool_pages) and
+ * all distinct.  pages_out: host (may be pinned), pool_pages * page_bytes. */
+int moe_pack_weights(const moe_shape* s, const void* W1, const void* W3, const void* W2,
+                     const int32_t* page_table, int64_t pool_pages, void* pages_out);
+/* Inverse of moe_pack_weights (host to host); used by tests. */
+int moe_unpack_weights(const moe_shape* s, const void* pages, const int32_t* page_table,
+                       int64_t pool_pages, void* W1, void* W3, void* W2);
+/* Checks a HOST copy of a page table: MOE_ERR_PAGE_NOT_RESIDENT if an entry is
+ * negative or >= pool_pages.  (Kernels also guard every entry they use: a bad
+ * entry is never dereferenced, the tile reads slot 0 instead and bit 0 of the
+ * device status word is set; see moe_workspace_layout.status.) */
+int moe_page_table_validate(const moe_shape* s, const int32_t* page_table_host, int64_t pool_pages);
+
+/* ------------------------------------------------------------------ workspace */
+
+typedef struct moe_workspace_layout {
+    /* byte offsets into the workspace of moe_layer, each 256-byte aligned */
+    size_t status;     /* int32[4]: [0] bit 0 = a page-table entry was not resident */
+    size_t topk_ids;   /* int32[T][k] */
+    size_t topk_w;     /* float[T][k] */
+    size_t counts;     /* int32[E] */
+    size_t offsets;    /* int32[E+1] */
+    size_t row_src;    /* int32[R] */
+    size_t row_of;     /* int32[R] */
+    size_t row_w;      /* float[R]: gate weight of each permuted row */
+    size_t scan;       /* scratch of the permutation kernels */
+    size_t x_perm;     /* dtype[R][H] */
+    size_t h;          /* dtype[R][F] */
+    size_t out;        /* float[R][H] */
+    size_t total;      /* bytes needed by moe_layer */
+    size_t permute_bytes; /* bytes moe_permute needs in its own workspace argument */
+} moe_workspace_layout;
+
+int moe_workspace_layout_get(const moe_shape* s, moe_workspace_layout* out);
+
+/* ------------------------------------------------------------------ the five calls */
+
+/* a1. Router.  logits = x Wr^T (+ bias); topk_ids[t] = the k largest logits in
+ * descending order (ties: lower expert index); topk_w[t] = softmax over those k
+ * logits.  x: device dtype[T][H]; Wr: device dtype[E][H]; bias: device float[E]
+ * or NULL; topk_ids: device int32[T][k]; topk_w: device float[T][k]; logits:
+ * device float[T][E] or NULL. */
+int moe_route(const moe_shape* s, const void* x, const void* Wr, const float* bias,
+              int32_t* topk_ids, float* topk_w, float* logits, void* stream);
+
+/* a2. Permutation by expert: histogram counts[E], exclusive scan offsets[E+1],
+ * stable placement (ascending flat index t*k+slot inside an expert):
+ * row_of[t*k+slot] = row, row_src[row] = t*k+slot, x_perm[row] = x[t].
+ * row_w (device float[R], may be NULL) receives topk_w[row_src[row]] when topk_w
+ * is given.  x / x_perm may both be NULL to skip the row copy.  workspace:
+ * device, at least moe_workspace_layout.permute_bytes. */
+int moe_permute(const moe_shape* s, const int32_t* topk_ids, const float* topk_w, const void* x,
+                int32_t* counts, int32_t* offsets, int32_t* row_src, int32_t* row_of,
+                float* row_w, void* x_perm, void* workspace, size_t workspace_bytes, void* stream);
+
+/* a3. Grouped SwiGLU expert FFN over paged weights.  For every row r of expert
+ * e (offsets[e] <= r < offsets[e+1]):
+ *   h[r] = dtype( silu(W1_e x_perm[r]) * (W3_e x_perm[r]) ),  out[r] = W2_e h[r]
+ * and out[r] *= row_w[r] when row_w != NULL.  x_perm: device dtype[R][H];
+ * offsets: device int32[E+1]; page_table: device int32[E][pages_per_expert];
+ * page_pool: device, pool_pages * page_bytes; h_ws: device dtype[R][F];
+ * out: device float[R][H]; status: device int32[4] or NULL (see above). */
+int moe_expert_ffn(const moe_shape* s, const void* x_perm, const int32_t* offsets,
+                   const int32_t* page_table, const void* page_pool, int64_t pool_pages,
+                   const float* row_w, void* h_ws, float* out, int32_t* status, void* stream);
+
+/* a4. Un-permute and combine: y[t] = sum_slot w * out[row_of[t*k+slot]], with
+ * w = topk_w[t][slot], or 1 when topk_w == NULL (weight already applied).
+ * out: device float[R][H]; y: device float[T][H]. */
+int moe_combine(const moe_shape* s, const float* out, const int32_t* row_of,
+                const float* topk_w, float* y, void* stream);
+
+/* a5. The whole layer in one call, on one stream, without host synchronisation.
+ * Intermediates live in `workspace` at the offsets of moe_workspace_layout_get
+ * and may be inspected after the stream has finished. */
+int moe_layer(const moe_shape* s, const void* x, const void* Wr, const float* bias,
+              const int32_t* page_table, const void* page_pool, int64_t pool_pages,
+              float* y, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------ streamed pages
+ *
+ * Expert pages live in pinned host memory; the library copies them, expert by
+ * expert, into a two-slot device region (2 * pages_per_expert pages: the
+ * paper's double buffer of appendix A.1) on `copy_stream` while the expert
+ * GEMMs of the previous expert run on `stream`.
+ */
+typedef struct moe_streamer moe_streamer;
+
+/* host_pages: pinned, host_pool_pages * page_bytes; host_page_table: host
+ * int32[E][pages_per_expert], slots into host_pages; slots: device,
+ * 2 * pages_per_expert * page_bytes; slot_table: device int32[2][pages_per_expert],
+ * filled here.  Creates HIP events (not a hot call). */
+int moe_stream_create(const moe_shape* s, const void* host_pages, int64_t host_pool_pages,
+                      const int32_t* host_page_table, void* slots, int32_t* slot_table,
+                      moe_streamer** out);
+int moe_stream_destroy(moe_streamer* st);
+/* Same results as moe_expert_ffn / moe_layer with all pages resident. */
+int moe_expert_ffn_streamed(moe_streamer* st, const void* x_perm, const int32_t* offsets,
+                            const float* row_w, void* h_ws, float* out, int32_t* status,
+                            void* stream, void* copy_stream);
+int moe_layer_streamed(moe_streamer* st, const void* x, const void* Wr, const float* bias,
+                       float* y, void* workspace, size_t workspace_bytes,
+                       void* stream, void* copy_stream);
+
+/* ------------------------------------------------------------------ tuning knobs
+ * Named integer options for experiments (kernel variants, tile order); unknown
+ * names give MOE_ERR_INVALID_ARG.  Defaults are the measured best. */
+int moe_set_option(const char* name, int value);
+int moe_get_option(const char* name, int* value);
+
+/* ------------------------------------------------------------------ stage timing
+ * For measurements only.  While option "profile" is 1, moe_layer records HIP
+ * events on its stream around its stages (route, permute, gate/up GEMM, down
+ * GEMM, combine); the last MOE_PROFILE_RING calls are kept.  moe_profile_read
+ * must be called after the stream has been synchronised: it writes the average
+ * duration of each stage in milliseconds to avg_ms[MOE_PROFILE_STAGES], the
+ * number of calls averaged to *n_calls, and forgets them. */
+#define MOE_PROFILE_STAGES 5
+#define MOE_PROFILE_RING 256
+int moe_profile_read(double* avg_ms, int* n_calls);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H_ */

@@ -1,0 +1,401 @@
+"""ctypes binding of libmoe_hip.so (the C ABI of include/moe.h).
+
+Only argument marshalling happens here: tensors are checked (device, dtype,
+contiguity, shape), outputs and workspaces are allocated with torch, raw
+pointers and the current HIP stream are handed to the library.  Every step of
+the layer runs in the library's kernels.  If the library cannot be loaded the
+import of a symbol fails loudly; there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+from . import build as _build
+
+_i32, _i64, _vp, _sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+
+DTYPE_F32, DTYPE_BF16 = 0, 1
+MAX_EXPERTS = 64
+
+
+class MoEShape(ctypes.Structure):
+    """struct moe_shape: T, H (h1), F (h2), E (n_e), k, dtype, page_bytes."""
+    _fields_ = [("T", _i32), ("H", _i32), ("F", _i32), ("E", _i32), ("k", _i32), ("dtype", _i32),
+                ("page_bytes", _i64)]
+
+    @property
+    def R(self) -> int:
+        return self.T * self.k
+
+    @property
+    def torch_dtype(self):
+        return torch.bfloat16 if self.dtype == DTYPE_BF16 else torch.float32
+
+    def with_tokens(self, T: int) -> "MoEShape":
+        return MoEShape(T, self.H, self.F, self.E, self.k, self.dtype, self.page_bytes)
+
+
+class WorkspaceLayout(ctypes.Structure):
+    _fields_ = [(n, _sz) for n in ("status", "topk_ids", "topk_w", "counts", "offsets", "row_src", "row_of", "row_w",
+                                   "scan", "x_perm", "h", "out", "total", "permute_bytes")]
+
+
+class MoEError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib().moe_status_string(status).decode()
+        if status == -5:
+            msg += " (hipError %d)" % _lib().moe_last_hip_error()
+        super().__init__("%s: %s [%d]" % (where, msg, status))
+
+
+ERR_INVALID_ARG, ERR_UNSUPPORTED_DTYPE, ERR_WORKSPACE_TOO_SMALL, ERR_PAGE_NOT_RESIDENT, ERR_HIP = -1, -2, -3, -4, -5
+
+_SIGNATURES = {
+    "moe_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "moe_last_hip_error": (ctypes.c_int, []),
+    "moe_validate_shape": (ctypes.c_int, [_vp]),
+    "moe_tile_bytes": (ctypes.c_int, [_vp, _vp]),
+    "moe_pages_required": (ctypes.c_int, [_vp, _vp, _vp]),
+    "moe_pack_weights": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _i64, _vp]),
+    "moe_unpack_weights": (ctypes.c_int, [_vp, _vp, _vp, _i64, _vp, _vp, _vp]),
+    "moe_page_table_validate": (ctypes.c_int, [_vp, _vp, _i64]),
+    "moe_workspace_layout_get": (ctypes.c_int, [_vp, _vp]),
+    "moe_route": (ctypes.c_int, [_vp] * 8),
+    "moe_permute": (ctypes.c_int, [_vp] * 11 + [_sz, _vp]),
+    "moe_expert_ffn": (ctypes.c_int, [_vp] * 5 + [_i64] + [_vp] * 5),
+    "moe_combine": (ctypes.c_int, [_vp] * 6),
+    "moe_layer": (ctypes.c_int, [_vp] * 6 + [_i64, _vp, _vp, _sz, _vp]),
+    "moe_stream_create": (ctypes.c_int, [_vp, _vp, _i64, _vp, _vp, _vp, _vp]),
+    "moe_stream_destroy": (ctypes.c_int, [_vp]),
+    "moe_expert_ffn_streamed": (ctypes.c_int, [_vp] * 9),
+    "moe_layer_streamed": (ctypes.c_int, [_vp] * 6 + [_sz, _vp, _vp]),
+    "moe_set_option": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_int]),
+    "moe_get_option": (ctypes.c_int, [ctypes.c_char_p, _vp]),
+    "moe_profile_read": (ctypes.c_int, [_vp, _vp]),
+}
+EXPORTED_SYMBOLS = tuple(_SIGNATURES)
+
+_LIB = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def _lib():
+    global _LIB
+    if _LIB is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            path = _build.build(force=True)          # raises if hipcc is missing or the build fails
+        lib = ctypes.CDLL(path)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(lib, name)                   # AttributeError if a declared symbol is missing
+            fn.restype, fn.argtypes = res, args
+        _LIB = lib
+    return _LIB
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise MoEError(status, where)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev(t: Optional[torch.Tensor], dtype, shape, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name}: must be a CUDA/HIP device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    return t.data_ptr()
+
+
+def make_shape(T, H, F, E, k, dtype, page_bytes) -> MoEShape:
+    code = {"f32": 0, "bf16": 1, torch.float32: 0, torch.bfloat16: 1, 0: 0, 1: 1}[dtype]
+    return MoEShape(int(T), int(H), int(F), int(E), int(k), code, int(page_bytes))
+
+
+def validate_shape(s: MoEShape) -> int:
+    return _lib().moe_validate_shape(ctypes.byref(s))
+
+
+def tile_bytes(s: MoEShape) -> int:
+    v = _i64(0)
+    _check(_lib().moe_tile_bytes(ctypes.byref(s), ctypes.byref(v)), "moe_tile_bytes")
+    return v.value
+
+
+def pages_required(s: MoEShape):
+    """(pages_gu, pages_d) per expert."""
+    a, b = _i64(0), _i64(0)
+    _check(_lib().moe_pages_required(ctypes.byref(s), ctypes.byref(a), ctypes.byref(b)), "moe_pages_required")
+    return a.value, b.value
+
+
+def workspace_layout(s: MoEShape) -> WorkspaceLayout:
+    L = WorkspaceLayout()
+    _check(_lib().moe_workspace_layout_get(ctypes.byref(s), ctypes.byref(L)), "moe_workspace_layout_get")
+    return L
+
+
+def set_option(name: str, value: int):
+    _check(_lib().moe_set_option(name.encode(), int(value)), "moe_set_option(%s)" % name)
+
+
+def get_option(name: str) -> int:
+    v = ctypes.c_int(0)
+    _check(_lib().moe_get_option(name.encode(), ctypes.byref(v)), "moe_get_option(%s)" % name)
+    return v.value
+
+
+PROFILE_STAGES = ("route", "permute", "gemm_gate_up", "gemm_down", "combine")
+
+
+def profile_read():
+    """Average stage durations (ms) of the moe_layer calls made while option "profile" was 1,
+    as (dict stage -> ms, n_calls).  Synchronise the stream first."""
+    arr = (ctypes.c_double * len(PROFILE_STAGES))()
+    n = ctypes.c_int(0)
+    _check(_lib().moe_profile_read(arr, ctypes.byref(n)), "moe_profile_read")
+    return {name: arr[i] for i, name in enumerate(PROFILE_STAGES)}, n.value
+
+
+# ----------------------------------------------------------------------------- paged weights
+
+def _host(t: torch.Tensor, dtype, shape, name):
+    if t.is_cuda:
+        raise ValueError(f"{name}: must be a host tensor")
+    if t.dtype != dtype or not t.is_contiguous() or tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected contiguous {dtype} of shape {tuple(shape)}")
+    return t.data_ptr()
+
+
+def page_table_validate(s: MoEShape, page_table_host: torch.Tensor, pool_pages: int):
+    gu, d = pages_required(s)
+    p = _host(page_table_host, torch.int32, (s.E, gu + d), "page_table")
+    _check(_lib().moe_page_table_validate(ctypes.byref(s), p, int(pool_pages)), "moe_page_table_validate")
+
+
+def pack_weights(s: MoEShape, W1, W3, W2, page_table: torch.Tensor, pool_pages: int, pin: bool = False) -> torch.Tensor:
+    """Host packer: dense W1/W3 [E,F,H], W2 [E,H,F] -> uint8 [pool_pages, page_bytes] (optionally pinned)."""
+    gu, d = pages_required(s)
+    dt = s.torch_dtype
+    p1 = _host(W1, dt, (s.E, s.F, s.H), "W1")
+    p3 = _host(W3, dt, (s.E, s.F, s.H), "W3")
+    p2 = _host(W2, dt, (s.E, s.H, s.F), "W2")
+    pt = _host(page_table, torch.int32, (s.E, gu + d), "page_table")
+    pages = torch.zeros((int(pool_pages), s.page_bytes), dtype=torch.uint8, pin_memory=pin)
+    _check(_lib().moe_pack_weights(ctypes.byref(s), p1, p3, p2, pt, int(pool_pages), pages.data_ptr()), "moe_pack_weights")
+    return pages
+
+
+def unpack_weights(s: MoEShape, pages: torch.Tensor, page_table: torch.Tensor):
+    gu, d = pages_required(s)
+    dt = s.torch_dtype
+    pool_pages = pages.shape[0]
+    pg = _host(pages, torch.uint8, (pool_pages, s.page_bytes), "pages")
+    pt = _host(page_table, torch.int32, (s.E, gu + d), "page_table")
+    W1 = torch.zeros((s.E, s.F, s.H), dtype=dt)
+    W3 = torch.zeros((s.E, s.F, s.H), dtype=dt)
+    W2 = torch.zeros((s.E, s.H, s.F), dtype=dt)
+    _check(_lib().moe_unpack_weights(ctypes.byref(s), pg, pt, int(pool_pages), W1.data_ptr(), W3.data_ptr(), W2.data_ptr()),
+           "moe_unpack_weights")
+    return W1, W3, W2
+
+
+# ----------------------------------------------------------------------------- the five calls
+
+def moe_route(s: MoEShape, x, Wr, bias=None, want_logits: bool = False, stream=None):
+    """-> (topk_ids int32 [T,k], topk_w float32 [T,k], logits float32 [T,E] or None)"""
+    dt = s.torch_dtype
+    px = _dev(x, dt, (s.T, s.H), "x")
+    pw = _dev(Wr, dt, (s.E, s.H), "Wr")
+    pb = _dev(bias, torch.float32, (s.E,), "bias")
+    ids = torch.empty((s.T, s.k), dtype=torch.int32, device=x.device)
+    w = torch.empty((s.T, s.k), dtype=torch.float32, device=x.device)
+    logits = torch.empty((s.T, s.E), dtype=torch.float32, device=x.device) if want_logits else None
+    _check(_lib().moe_route(ctypes.byref(s), px, pw, pb, ids.data_ptr(), w.data_ptr(),
+                            None if logits is None else logits.data_ptr(), _stream(stream)), "moe_route")
+    return ids, w, logits
+
+
+def moe_permute(s: MoEShape, topk_ids, x=None, topk_w=None, stream=None):
+    """-> dict(counts[E], offsets[E+1], row_src[R], row_of[R], row_w[R] or None, x_perm[R,H] or None)"""
+    dev = topk_ids.device
+    pi = _dev(topk_ids, torch.int32, (s.T, s.k), "topk_ids")
+    pw = _dev(topk_w, torch.float32, (s.T, s.k), "topk_w")
+    px = _dev(x, s.torch_dtype, (s.T, s.H), "x")
+    R = s.R
+    counts = torch.empty(s.E, dtype=torch.int32, device=dev)
+    offsets = torch.empty(s.E + 1, dtype=torch.int32, device=dev)
+    row_src = torch.empty(R, dtype=torch.int32, device=dev)
+    row_of = torch.empty(R, dtype=torch.int32, device=dev)
+    row_w = torch.empty(R, dtype=torch.float32, device=dev) if topk_w is not None else None
+    x_perm = torch.empty((R, s.H), dtype=s.torch_dtype, device=dev) if x is not None else None
+    wsb = workspace_layout(s).permute_bytes
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+    _check(_lib().moe_permute(ctypes.byref(s), pi, pw, px, counts.data_ptr(), offsets.data_ptr(), row_src.data_ptr(),
+                              row_of.data_ptr(), None if row_w is None else row_w.data_ptr(),
+                              None if x_perm is None else x_perm.data_ptr(), ws.data_ptr(), ws.numel(),
+                              _stream(stream)), "moe_permute")
+    return dict(counts=counts, offsets=offsets, row_src=row_src, row_of=row_of, row_w=row_w, x_perm=x_perm)
+
+
+def moe_expert_ffn(s: MoEShape, x_perm, offsets, page_table, page_pool, row_w=None, status=None, stream=None):
+    """-> (h [R,F] dtype, out [R,H] float32)"""
+    dev = x_perm.device
+    R = s.R
+    gu, d = pages_required(s)
+    px = _dev(x_perm, s.torch_dtype, (R, s.H), "x_perm")
+    po = _dev(offsets, torch.int32, (s.E + 1,), "offsets")
+    pt = _dev(page_table, torch.int32, (s.E, gu + d), "page_table")
+    pp = _dev(page_pool, torch.uint8, None, "page_pool")
+    if page_pool.dim() != 2 or page_pool.shape[1] != s.page_bytes:
+        raise ValueError("page_pool: expected uint8 [pool_pages, page_bytes]")
+    pr = _dev(row_w, torch.float32, (R,), "row_w")
+    ps = _dev(status, torch.int32, (4,), "status")
+    h = torch.empty((R, s.F), dtype=s.torch_dtype, device=dev)
+    out = torch.empty((R, s.H), dtype=torch.float32, device=dev)
+    _check(_lib().moe_expert_ffn(ctypes.byref(s), px, po, pt, pp, int(page_pool.shape[0]), pr, h.data_ptr(),
+                                 out.data_ptr(), ps, _stream(stream)), "moe_expert_ffn")
+    return h, out
+
+
+def moe_combine(s: MoEShape, out, row_of, topk_w=None, stream=None):
+    """-> y float32 [T,H]"""
+    po = _dev(out, torch.float32, (s.R, s.H), "out")
+    pr = _dev(row_of, torch.int32, (s.R,), "row_of")
+    pw = _dev(topk_w, torch.float32, (s.T, s.k), "topk_w")
+    y = torch.empty((s.T, s.H), dtype=torch.float32, device=out.device)
+    _check(_lib().moe_combine(ctypes.byref(s), po, pr, pw, y.data_ptr(), _stream(stream)), "moe_combine")
+    return y
+
+
+class Workspace:
+    """Device scratch of moe_layer plus typed views of the intermediates it leaves behind."""
+
+    def __init__(self, s: MoEShape, device="cuda"):
+        self.shape = s
+        self.layout = workspace_layout(s)
+        self.buf = torch.empty(max(self.layout.total, 256), dtype=torch.uint8, device=device)
+        if self.buf.data_ptr() % 256:
+            raise RuntimeError("allocator returned an unaligned workspace")
+
+    def view(self, name: str) -> torch.Tensor:
+        s, L = self.shape, self.layout
+        R = s.R
+        esz = 2 if s.dtype == DTYPE_BF16 else 4
+        spec = {
+            "status": (torch.int32, (4,), 16), "topk_ids": (torch.int32, (s.T, s.k), R * 4),
+            "topk_w": (torch.float32, (s.T, s.k), R * 4), "counts": (torch.int32, (s.E,), s.E * 4),
+            "offsets": (torch.int32, (s.E + 1,), (s.E + 1) * 4), "row_src": (torch.int32, (R,), R * 4),
+            "row_of": (torch.int32, (R,), R * 4), "row_w": (torch.float32, (R,), R * 4),
+            "x_perm": (s.torch_dtype, (R, s.H), R * s.H * esz), "h": (s.torch_dtype, (R, s.F), R * s.F * esz),
+            "out": (torch.float32, (R, s.H), R * s.H * 4),
+        }[name]
+        off = getattr(L, name)
+        return self.buf[off:off + spec[2]].view(spec[0]).view(spec[1])
+
+
+def moe_layer(s: MoEShape, x, Wr, page_table, page_pool, bias=None, workspace: Optional[Workspace] = None,
+              y: Optional[torch.Tensor] = None, stream=None):
+    """-> (y float32 [T,H], workspace)"""
+    gu, d = pages_required(s)
+    dt = s.torch_dtype
+    px = _dev(x, dt, (s.T, s.H), "x")
+    pw = _dev(Wr, dt, (s.E, s.H), "Wr")
+    pb = _dev(bias, torch.float32, (s.E,), "bias")
+    pt = _dev(page_table, torch.int32, (s.E, gu + d), "page_table")
+    pp = _dev(page_pool, torch.uint8, None, "page_pool")
+    if page_pool.dim() != 2 or page_pool.shape[1] != s.page_bytes:
+        raise ValueError("page_pool: expected uint8 [pool_pages, page_bytes]")
+    if workspace is None:
+        workspace = Workspace(s, x.device)
+    if y is None:
+        y = torch.empty((s.T, s.H), dtype=torch.float32, device=x.device)
+    _dev(y, torch.float32, (s.T, s.H), "y")
+    _check(_lib().moe_layer(ctypes.byref(s), px, pw, pb, pt, pp, int(page_pool.shape[0]), y.data_ptr(),
+                            workspace.buf.data_ptr(), workspace.buf.numel(), _stream(stream)), "moe_layer")
+    return y, workspace
+
+
+# ----------------------------------------------------------------------------- streamed pages
+
+class Streamer:
+    """Expert pages in pinned host memory, streamed through a two-slot device region."""
+
+    def __init__(self, s: MoEShape, host_pages: torch.Tensor, host_page_table: torch.Tensor, device="cuda"):
+        gu, d = pages_required(s)
+        self.shape, self.ppe = s, gu + d
+        if not host_pages.is_pinned():
+            raise ValueError("host_pages must be pinned host memory")
+        pg = _host(host_pages, torch.uint8, (host_pages.shape[0], s.page_bytes), "host_pages")
+        pt = _host(host_page_table, torch.int32, (s.E, self.ppe), "host_page_table")
+        self.host_pages, self.host_page_table = host_pages, host_page_table
+        self.slots = torch.empty((2 * self.ppe, s.page_bytes), dtype=torch.uint8, device=device)
+        self.slot_table = torch.empty((2, self.ppe), dtype=torch.int32, device=device)
+        self.copy_stream = torch.cuda.Stream(device=device)
+        handle = _vp(0)
+        _check(_lib().moe_stream_create(ctypes.byref(s), pg, int(host_pages.shape[0]), pt, self.slots.data_ptr(),
+                                        self.slot_table.data_ptr(), ctypes.byref(handle)), "moe_stream_create")
+        self.handle = handle
+
+    def close(self):
+        if self.handle:
+            torch.cuda.synchronize()
+            _check(_lib().moe_stream_destroy(self.handle), "moe_stream_destroy")
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def moe_expert_ffn_streamed(st: Streamer, x_perm, offsets, row_w=None, status=None, stream=None):
+    s = st.shape
+    R = s.R
+    px = _dev(x_perm, s.torch_dtype, (R, s.H), "x_perm")
+    po = _dev(offsets, torch.int32, (s.E + 1,), "offsets")
+    pr = _dev(row_w, torch.float32, (R,), "row_w")
+    ps = _dev(status, torch.int32, (4,), "status")
+    h = torch.empty((R, s.F), dtype=s.torch_dtype, device=x_perm.device)
+    out = torch.empty((R, s.H), dtype=torch.float32, device=x_perm.device)
+    _check(_lib().moe_expert_ffn_streamed(st.handle, px, po, pr, h.data_ptr(), out.data_ptr(), ps, _stream(stream),
+                                          st.copy_stream.cuda_stream), "moe_expert_ffn_streamed")
+    return h, out
+
+
+def moe_layer_streamed(st: Streamer, x, Wr, bias=None, workspace: Optional[Workspace] = None,
+                       y: Optional[torch.Tensor] = None, stream=None):
+    s = st.shape
+    dt = s.torch_dtype
+    px = _dev(x, dt, (s.T, s.H), "x")
+    pw = _dev(Wr, dt, (s.E, s.H), "Wr")
+    pb = _dev(bias, torch.float32, (s.E,), "bias")
+    if workspace is None:
+        workspace = Workspace(s, x.device)
+    if y is None:
+        y = torch.empty((s.T, s.H), dtype=torch.float32, device=x.device)
+    _dev(y, torch.float32, (s.T, s.H), "y")
+    _check(_lib().moe_layer_streamed(st.handle, px, pw, pb, y.data_ptr(), workspace.buf.data_ptr(),
+                                     workspace.buf.numel(), _stream(stream), st.copy_stream.cuda_stream),
+           "moe_layer_streamed")
+    return y, workspace

@@ -1,0 +1,521 @@
+// Host side of the C ABI: argument checks, page geometry, the weight packer,
+// workspace layout, and the entry points that enqueue the kernels.
+#include <algorithm>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+#include "moe_internal.h"
+
+namespace moe {
+
+static thread_local int g_last_hip_error = 0;
+void set_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+
+// ---- options ----------------------------------------------------------------
+static int g_opts[OPT_COUNT] = {
+    /*OPT_FFN_VARIANT*/ 1,   // 0: synchronous single-buffer loop, 1: double-buffered direct-to-LDS loop
+    /*OPT_XCD_REMAP*/ 1,     // 1: tiles are dealt to the 8 XCDs in contiguous chunks
+    /*OPT_PROFILE*/ 0,       // 1: moe_layer records stage events (see moe_profile_read)
+};
+static const char* g_opt_names[OPT_COUNT] = {"ffn_variant", "xcd_remap", "profile"};
+int get_opt(int id) { return g_opts[id]; }
+
+int validate_shape(const moe_shape* s) {
+    if (!s) return MOE_ERR_INVALID_ARG;
+    if (s->dtype != MOE_DTYPE_F32 && s->dtype != MOE_DTYPE_BF16) return MOE_ERR_UNSUPPORTED_DTYPE;
+    if (s->T < 0 || s->H <= 0 || s->F <= 0 || s->E < 1 || s->E > MOE_MAX_EXPERTS) return MOE_ERR_INVALID_ARG;
+    if (s->k < 1 || s->k > s->E) return MOE_ERR_INVALID_ARG;
+    if (s->H % kTileN != 0 || s->F % kTileN != 0) return MOE_ERR_INVALID_ARG;
+    if ((int64_t)s->T * s->k > (int64_t)0x3fffffff) return MOE_ERR_INVALID_ARG;
+    const int64_t tile = (int64_t)kTileN * kTileK * (s->dtype == MOE_DTYPE_BF16 ? 2 : 4);
+    if (s->page_bytes <= 0 || s->page_bytes % tile != 0) return MOE_ERR_INVALID_ARG;
+    return MOE_OK;
+}
+
+Geom geometry(const moe_shape& s) {
+    Geom g;
+    g.esize = s.dtype == MOE_DTYPE_BF16 ? 2 : 4;
+    g.tile_bytes = (int64_t)kTileN * kTileK * g.esize;
+    g.tpp = s.page_bytes / g.tile_bytes;
+    g.kt_gu = s.H / kTileK;
+    g.ft = s.F / kTileN;
+    g.tiles_gu = 2 * g.ft * g.kt_gu;
+    g.kt_d = s.F / kTileK;
+    g.dt = s.H / kTileN;
+    g.tiles_d = g.dt * g.kt_d;
+    g.pages_gu = (g.tiles_gu + g.tpp - 1) / g.tpp;
+    g.pages_d = (g.tiles_d + g.tpp - 1) / g.tpp;
+    g.ppe = g.pages_gu + g.pages_d;
+    return g;
+}
+
+// ---- packer -------------------------------------------------------------------
+// Copies one 128 x 64 tile between a dense row-major matrix (leading dimension
+// ld elements) and its page image.  to_page: dense -> page, else page -> dense.
+static void copy_tile(char* page_tile, char* dense, int64_t ld, int esize, bool to_page) {
+    const int row_bytes = kTileK * esize;
+    const int chunks = row_bytes / 16;
+    for (int n = 0; n < kTileN; ++n) {
+        char* prow = page_tile + (int64_t)n * row_bytes;
+        char* drow = dense + (int64_t)n * ld * esize;
+        for (int c = 0; c < chunks; ++c) {
+            const int pos = (c & ~7) | ((c & 7) ^ (n & 7));
+            if (to_page) std::memcpy(prow + pos * 16, drow + c * 16, 16);
+            else std::memcpy(drow + c * 16, prow + pos * 16, 16);
+        }
+    }
+}
+
+static int check_table_host(const moe_shape& s, const Geom& g, const int32_t* table, int64_t pool_pages,
+                            bool need_distinct) {
+    std::vector<char> seen;
+    if (need_distinct) seen.assign((size_t)pool_pages, 0);
+    for (int64_t i = 0; i < (int64_t)s.E * g.ppe; ++i) {
+        const int32_t v = table[i];
+        if (v < 0 || v >= pool_pages) return MOE_ERR_PAGE_NOT_RESIDENT;
+        if (need_distinct) {
+            if (seen[(size_t)v]) return MOE_ERR_INVALID_ARG;
+            seen[(size_t)v] = 1;
+        }
+    }
+    return MOE_OK;
+}
+
+static int pack_or_unpack(const moe_shape* s, char* W1, char* W3, char* W2, const int32_t* table,
+                          int64_t pool_pages, char* pages, bool to_page) {
+    int rc = validate_shape(s);
+    if (rc != MOE_OK) return rc;
+    if (!W1 || !W3 || !W2 || !table || !pages || pool_pages <= 0) return MOE_ERR_INVALID_ARG;
+    const Geom g = geometry(*s);
+    rc = check_table_host(*s, g, table, pool_pages, true);
+    if (rc != MOE_OK) return rc;
+    const int64_t H = s->H, F = s->F;
+    auto work = [&](int e) {
+        const int32_t* row = table + (int64_t)e * g.ppe;
+        auto tile_ptr = [&](int64_t group_base, int64_t ti) {
+            return pages + (int64_t)row[group_base + ti / g.tpp] * s->page_bytes + (ti % g.tpp) * g.tile_bytes;
+        };
+        if (to_page) {   // zero the padding of the last page of each group
+            const int64_t pad_gu = g.pages_gu * g.tpp - g.tiles_gu, pad_d = g.pages_d * g.tpp - g.tiles_d;
+            for (int64_t i = 0; i < pad_gu; ++i) std::memset(tile_ptr(0, g.tiles_gu + i), 0, (size_t)g.tile_bytes);
+            for (int64_t i = 0; i < pad_d; ++i) std::memset(tile_ptr(g.pages_gu, g.tiles_d + i), 0, (size_t)g.tile_bytes);
+        }
+        for (int64_t f = 0; f < g.ft; ++f)
+            for (int w = 0; w < 2; ++w)
+                for (int64_t kt = 0; kt < g.kt_gu; ++kt) {
+                    char* dense = (w == 0 ? W1 : W3) + (((int64_t)e * F + f * kTileN) * H + kt * kTileK) * g.esize;
+                    copy_tile(tile_ptr(0, (f * 2 + w) * g.kt_gu + kt), dense, H, g.esize, to_page);
+                }
+        for (int64_t d = 0; d < g.dt; ++d)
+            for (int64_t kt = 0; kt < g.kt_d; ++kt) {
+                char* dense = W2 + (((int64_t)e * H + d * kTileN) * F + kt * kTileK) * g.esize;
+                copy_tile(tile_ptr(g.pages_gu, d * g.kt_d + kt), dense, F, g.esize, to_page);
+            }
+    };
+    const int nthr = std::max(1, std::min<int>(s->E, (int)std::min(16u, std::max(1u, std::thread::hardware_concurrency()))));
+    std::vector<std::thread> pool;
+    for (int t = 0; t < nthr; ++t)
+        pool.emplace_back([&, t]() { for (int e = t; e < s->E; e += nthr) work(e); });
+    for (auto& th : pool) th.join();
+    return MOE_OK;
+}
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static int layout(const moe_shape& s, moe_workspace_layout* L) {
+    const Geom g = geometry(s);
+    const size_t R = (size_t)s.T * s.k, A = 256;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + std::max<size_t>(bytes, 4), A); return o; };
+    L->status = take(16);
+    L->topk_ids = take(R * 4);
+    L->topk_w = take(R * 4);
+    L->counts = take((size_t)s.E * 4);
+    L->offsets = take((size_t)(s.E + 1) * 4);
+    L->row_src = take(R * 4);
+    L->row_of = take(R * 4);
+    L->row_w = take(R * 4);
+    L->permute_bytes = permute_workspace_bytes(s);
+    L->scan = take(L->permute_bytes);
+    L->x_perm = take(R * s.H * g.esize);
+    L->h = take(R * s.F * g.esize);
+    L->out = take(R * s.H * 4);
+    L->total = off;
+    return MOE_OK;
+}
+
+// ---- stage timing ---------------------------------------------------------------
+struct Profiler {
+    bool ready = false;
+    hipEvent_t ev[MOE_PROFILE_RING][MOE_PROFILE_STAGES + 1];
+    int next = 0, count = 0;
+};
+static Profiler g_prof;
+
+static int prof_slot() {
+    if (!g_opts[OPT_PROFILE]) return -1;
+    if (!g_prof.ready) {
+        for (int i = 0; i < MOE_PROFILE_RING; ++i)
+            for (int j = 0; j <= MOE_PROFILE_STAGES; ++j)
+                if (hipEventCreate(&g_prof.ev[i][j]) != hipSuccess) return -1;
+        g_prof.ready = true;
+    }
+    const int slot = g_prof.next;
+    g_prof.next = (g_prof.next + 1) % MOE_PROFILE_RING;
+    if (g_prof.count < MOE_PROFILE_RING) ++g_prof.count;
+    return slot;
+}
+static void prof_mark(int slot, int j, hipStream_t st) {
+    if (slot >= 0) (void)hipEventRecord(g_prof.ev[slot][j], st);
+}
+static hipEvent_t prof_event(int slot, int j) { return slot >= 0 ? g_prof.ev[slot][j] : nullptr; }
+
+__global__ void clear_status_kernel(int32_t* status) {
+    if (threadIdx.x < 4) status[threadIdx.x] = 0;
+}
+
+// The body of the layer on one stream; `ffn` runs the expert FFN stage.
+template <class FfnFn>
+static int layer_body(const moe_shape& s, const void* x, const void* Wr, const float* bias, float* y,
+                      char* ws, hipStream_t st, FfnFn ffn) {
+    moe_workspace_layout L;
+    layout(s, &L);
+    int32_t* status = (int32_t*)(ws + L.status);
+    int32_t* ids = (int32_t*)(ws + L.topk_ids);
+    float* w = (float*)(ws + L.topk_w);
+    int32_t* counts = (int32_t*)(ws + L.counts);
+    int32_t* offsets = (int32_t*)(ws + L.offsets);
+    int32_t* row_src = (int32_t*)(ws + L.row_src);
+    int32_t* row_of = (int32_t*)(ws + L.row_of);
+    float* row_w = (float*)(ws + L.row_w);
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, st, status);   // a kernel, so the call can be graph-captured
+    MOE_HIP_TRY(hipGetLastError());
+    const int ps = prof_slot();
+    prof_mark(ps, 0, st);
+    int rc = launch_route(s, x, Wr, bias, ids, w, nullptr, st);
+    if (rc != MOE_OK) return rc;
+    prof_mark(ps, 1, st);
+    rc = launch_permute(s, ids, w, x, counts, offsets, row_src, row_of, row_w, ws + L.x_perm, ws + L.scan, st);
+    if (rc != MOE_OK) return rc;
+    prof_mark(ps, 2, st);
+    rc = ffn(ws + L.x_perm, offsets, row_w, ws + L.h, (float*)(ws + L.out), status, prof_event(ps, 3));
+    if (rc != MOE_OK) return rc;
+    prof_mark(ps, 4, st);
+    // the gate weight was applied in the down-projection epilogue: plain sum here
+    rc = launch_combine(s, (const float*)(ws + L.out), row_of, nullptr, y, st);
+    prof_mark(ps, 5, st);
+    return rc;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" {
+
+const char* moe_status_string(int status) {
+    switch (status) {
+        case MOE_OK: return "ok";
+        case MOE_ERR_INVALID_ARG: return "invalid argument";
+        case MOE_ERR_UNSUPPORTED_DTYPE: return "unsupported dtype";
+        case MOE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case MOE_ERR_PAGE_NOT_RESIDENT: return "page not resident";
+        case MOE_ERR_HIP: return "HIP error";
+        default: return "unknown status";
+    }
+}
+
+int moe_last_hip_error(void) { return g_last_hip_error; }
+
+int moe_validate_shape(const moe_shape* s) { return validate_shape(s); }
+
+int moe_tile_bytes(const moe_shape* s, int64_t* tile_bytes) {
+    int rc = validate_shape(s);
+    if (rc != MOE_OK) return rc;
+    if (!tile_bytes) return MOE_ERR_INVALID_ARG;
+    *tile_bytes = geometry(*s).tile_bytes;
+    return MOE_OK;
+}
+
+int moe_pages_required(const moe_shape* s, int64_t* pages_gu, int64_t* pages_d) {
+    int rc = validate_shape(s);
+    if (rc != MOE_OK) return rc;
+    if (!pages_gu || !pages_d) return MOE_ERR_INVALID_ARG;
+    const Geom g = geometry(*s);
+    *pages_gu = g.pages_gu;
+    *pages_d = g.pages_d;
+    return MOE_OK;
+}
+
+int moe_pack_weights(const moe_shape* s, const void* W1, const void* W3, const void* W2,
+                     const int32_t* page_table, int64_t pool_pages, void* pages_out) {
+    return pack_or_unpack(s, (char*)W1, (char*)W3, (char*)W2, page_table, pool_pages, (char*)pages_out, true);
+}
+
+int moe_unpack_weights(const moe_shape* s, const void* pages, const int32_t* page_table,
+                       int64_t pool_pages, void* W1, void* W3, void* W2) {
+    return pack_or_unpack(s, (char*)W1, (char*)W3, (char*)W2, page_table, pool_pages, (char*)pages, false);
+}
+
+int moe_page_table_validate(const moe_shape* s, const int32_t* page_table_host, int64_t pool_pages) {
+    int rc = validate_shape(s);
+    if (rc != MOE_OK) return rc;
+    if (!page_table_host || pool_pages <= 0) return MOE_ERR_INVALID_ARG;
+    return check_table_host(*s, geometry(*s), page_table_host, pool_pages, false);
+}
+
+int moe_workspace_layout_get(const moe_shape* s, moe_workspace_layout* out) {
+    int rc = validate_shape(s);
+    if (rc != MOE_OK) return rc;
+    if (!out) return MOE_ERR_INVALID_ARG;
+    return layout(*s, out);
+}
+
+int moe_route(const moe_shape* s, const void* x, const void* Wr, const float* bias,
+              int32_t* topk_ids, float* topk_w, float* logits, void* stream) {
+    int rc = validate_shape(s);
+    if (rc != MOE_OK) return rc;
+    if (s->T == 0) return MOE_OK;
+    if (!x || !Wr || !topk_ids || !topk_w) return MOE_ERR_INVALID_ARG;
+    return launch_route(*s, x, Wr, bias, topk_ids, topk_w, logits, (hipStream_t)stream);
+}
+
+int moe_permute(const moe_shape* s, const int32_t* topk_ids, const float* topk_w, const void* x,
+                int32_t* counts, int32_t* offsets, int32_t* row_src, int32_t* row_of,
+                float* row_w, void* x_perm, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = validate_shape(s);
+    if (rc != MOE_OK) return rc;
+    if (!counts || !offsets) return MOE_ERR_INVALID_ARG;
+    if (s->T > 0 && (!topk_ids || !row_src || !row_of)) return MOE_ERR_INVALID_ARG;
+    if ((x == nullptr) != (x_perm == nullptr)) return MOE_ERR_INVALID_ARG;
+    if (row_w && !topk_w) return MOE_ERR_INVALID_ARG;
+    if (!workspace) return MOE_ERR_INVALID_ARG;
+    if (workspace_bytes < permute_workspace_bytes(*s)) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    return launch_permute(*s, topk_ids, topk_w, x, counts, offsets, row_src, row_of, row_w, x_perm,
+                          workspace, (hipStream_t)stream);
+}
+
+int moe_expert_ffn(const moe_shape* s, const void* x_perm, const int32_t* offsets,
+                   const int32_t* page_table, const void* page_pool, int64_t pool_pages,
+                   const float* row_w, void* h_ws, float* out, int32_t* status, void* stream) {
+    int rc = validate_shape(s);
+    if (rc != MOE_OK) return rc;
+    if (s->T == 0) return MOE_OK;
+    if (!x_perm || !offsets || !page_table || !page_pool || !h_ws || !out || pool_pages <= 0)
+        return MOE_ERR_INVALID_ARG;
+    FfnArgs a{x_perm, offsets, page_table, (const char*)page_pool, pool_pages, row_w, h_ws, out, status,
+              0, s->E, 0, nullptr};
+    return launch_expert_ffn(*s, a, (hipStream_t)stream);
+}
+
+int moe_combine(const moe_shape* s, const float* out, const int32_t* row_of,
+                const float* topk_w, float* y, void* stream) {
+    int rc = validate_shape(s);
+    if (rc != MOE_OK) return rc;
+    if (s->T == 0) return MOE_OK;
+    if (!out || !row_of || !y) return MOE_ERR_INVALID_ARG;
+    return launch_combine(*s, out, row_of, topk_w, y, (hipStream_t)stream);
+}
+
+int moe_layer(const moe_shape* s, const void* x, const void* Wr, const float* bias,
+              const int32_t* page_table, const void* page_pool, int64_t pool_pages,
+              float* y, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = validate_shape(s);
+    if (rc != MOE_OK) return rc;
+    if (s->T == 0) return MOE_OK;
+    if (!x || !Wr || !page_table || !page_pool || !y || !workspace || pool_pages <= 0)
+        return MOE_ERR_INVALID_ARG;
+    moe_workspace_layout L;
+    layout(*s, &L);
+    if (workspace_bytes < L.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const moe_shape sh = *s;
+    return layer_body(sh, x, Wr, bias, y, (char*)workspace, st,
+                      [&](const void* xp, const int32_t* offsets, const float* row_w, void* h, float* out,
+                          int32_t* status, hipEvent_t mid) {
+                          FfnArgs a{xp, offsets, page_table, (const char*)page_pool, pool_pages, row_w, h, out,
+                                    status, 0, sh.E, 0, mid};
+                          return launch_expert_ffn(sh, a, st);
+                      });
+}
+
+int moe_set_option(const char* name, int value) {
+    if (!name) return MOE_ERR_INVALID_ARG;
+    for (int i = 0; i < OPT_COUNT; ++i)
+        if (std::strcmp(name, g_opt_names[i]) == 0) {
+            g_opts[i] = value;
+            return MOE_OK;
+        }
+    return MOE_ERR_INVALID_ARG;
+}
+
+int moe_profile_read(double* avg_ms, int* n_calls) {
+    if (!avg_ms || !n_calls) return MOE_ERR_INVALID_ARG;
+    for (int j = 0; j < MOE_PROFILE_STAGES; ++j) avg_ms[j] = 0.0;
+    *n_calls = 0;
+    if (!g_prof.ready || g_prof.count == 0) return MOE_OK;
+    const int n = g_prof.count;
+    for (int i = 0; i < n; ++i) {
+        const int slot = ((g_prof.next - 1 - i) % MOE_PROFILE_RING + MOE_PROFILE_RING) % MOE_PROFILE_RING;
+        for (int j = 0; j < MOE_PROFILE_STAGES; ++j) {
+            float ms = 0.f;
+            MOE_HIP_TRY(hipEventElapsedTime(&ms, g_prof.ev[slot][j], g_prof.ev[slot][j + 1]));
+            avg_ms[j] += ms;
+        }
+    }
+    for (int j = 0; j < MOE_PROFILE_STAGES; ++j) avg_ms[j] /= n;
+    *n_calls = n;
+    g_prof.count = 0;
+    return MOE_OK;
+}
+
+int moe_get_option(const char* name, int* value) {
+    if (!name || !value) return MOE_ERR_INVALID_ARG;
+    for (int i = 0; i < OPT_COUNT; ++i)
+        if (std::strcmp(name, g_opt_names[i]) == 0) {
+            *value = g_opts[i];
+            return MOE_OK;
+        }
+    return MOE_ERR_INVALID_ARG;
+}
+
+}  // extern "C"
+
+// ---- streamed pages -------------------------------------------------------------
+// One expert's pages are copied into slot (e & 1) on the copy stream while the
+// GEMMs of expert e-1 read the other slot on the compute stream.
+struct moe_streamer {
+    moe_shape shape;
+    Geom geom;
+    const char* host_pages;
+    std::vector<int32_t> host_table;   // [E][ppe]
+    char* slots;
+    int32_t* slot_table;               // device [2][ppe]
+    hipEvent_t loaded[2];              // slot s holds the pages of its current expert
+    hipEvent_t released[2];            // the GEMMs reading slot s have been enqueued and finished
+    hipEvent_t ready;                  // x_perm / offsets are ready on the compute stream
+};
+
+extern "C" {
+
+int moe_stream_create(const moe_shape* s, const void* host_pages, int64_t host_pool_pages,
+                      const int32_t* host_page_table, void* slots, int32_t* slot_table,
+                      moe_streamer** out) {
+    int rc = validate_shape(s);
+    if (rc != MOE_OK) return rc;
+    if (!host_pages || !host_page_table || !slots || !slot_table || !out || host_pool_pages <= 0)
+        return MOE_ERR_INVALID_ARG;
+    const Geom g = geometry(*s);
+    rc = check_table_host(*s, g, host_page_table, host_pool_pages, false);
+    if (rc != MOE_OK) return rc;
+    std::vector<int32_t> st_host((size_t)2 * g.ppe);
+    for (int sl = 0; sl < 2; ++sl)
+        for (int64_t p = 0; p < g.ppe; ++p) st_host[(size_t)sl * g.ppe + p] = (int32_t)(sl * g.ppe + p);
+    MOE_HIP_TRY(hipMemcpy(slot_table, st_host.data(), st_host.size() * 4, hipMemcpyHostToDevice));
+    moe_streamer* st = new moe_streamer();
+    st->shape = *s;
+    st->geom = g;
+    st->host_pages = (const char*)host_pages;
+    st->host_table.assign(host_page_table, host_page_table + (int64_t)s->E * g.ppe);
+    st->slots = (char*)slots;
+    st->slot_table = slot_table;
+    for (int i = 0; i < 2; ++i) {
+        MOE_HIP_TRY(hipEventCreateWithFlags(&st->loaded[i], hipEventDisableTiming));
+        MOE_HIP_TRY(hipEventCreateWithFlags(&st->released[i], hipEventDisableTiming));
+    }
+    MOE_HIP_TRY(hipEventCreateWithFlags(&st->ready, hipEventDisableTiming));
+    *out = st;
+    return MOE_OK;
+}
+
+int moe_stream_destroy(moe_streamer* st) {
+    if (!st) return MOE_ERR_INVALID_ARG;
+    for (int i = 0; i < 2; ++i) {
+        (void)hipEventDestroy(st->loaded[i]);
+        (void)hipEventDestroy(st->released[i]);
+    }
+    (void)hipEventDestroy(st->ready);
+    delete st;
+    return MOE_OK;
+}
+
+}  // extern "C"
+
+namespace moe {
+
+// Enqueue the copies of expert e's pages into slot e&1.  Runs of pages that are
+// consecutive in the host pool go out as one copy.
+static int enqueue_expert_copy(moe_streamer* st, int e, hipStream_t copy) {
+    const Geom& g = st->geom;
+    const int64_t pb = st->shape.page_bytes;
+    const int32_t* row = st->host_table.data() + (int64_t)e * g.ppe;
+    char* dst = st->slots + (int64_t)(e & 1) * g.ppe * pb;
+    int64_t p = 0;
+    while (p < g.ppe) {
+        int64_t q = p + 1;
+        while (q < g.ppe && row[q] == row[q - 1] + 1) ++q;
+        MOE_HIP_TRY(hipMemcpyAsync(dst + p * pb, st->host_pages + (int64_t)row[p] * pb, (size_t)((q - p) * pb),
+                                   hipMemcpyHostToDevice, copy));
+        p = q;
+    }
+    return MOE_OK;
+}
+
+static int ffn_streamed(moe_streamer* st, const void* x_perm, const int32_t* offsets, const float* row_w,
+                        void* h_ws, float* out, int32_t* status, hipStream_t comp, hipStream_t copy) {
+    const moe_shape& s = st->shape;
+    const Geom& g = st->geom;
+    // the copy stream must not overwrite a slot that GEMMs enqueued earlier on the
+    // compute stream (a previous call) may still read
+    MOE_HIP_TRY(hipEventRecord(st->ready, comp));
+    MOE_HIP_TRY(hipStreamWaitEvent(copy, st->ready, 0));
+    for (int e = 0; e < s.E; ++e) {
+        const int sl = e & 1;
+        if (e >= 2) MOE_HIP_TRY(hipStreamWaitEvent(copy, st->released[sl], 0));
+        int rc = enqueue_expert_copy(st, e, copy);
+        if (rc != MOE_OK) return rc;
+        MOE_HIP_TRY(hipEventRecord(st->loaded[sl], copy));
+        MOE_HIP_TRY(hipStreamWaitEvent(comp, st->loaded[sl], 0));
+        FfnArgs a{x_perm, offsets, st->slot_table, st->slots, 2 * g.ppe, row_w, h_ws, out, status, e, e + 1, 2, nullptr};
+        rc = launch_expert_ffn(s, a, comp);
+        if (rc != MOE_OK) return rc;
+        MOE_HIP_TRY(hipEventRecord(st->released[sl], comp));
+    }
+    return MOE_OK;
+}
+
+}  // namespace moe
+
+extern "C" {
+
+int moe_expert_ffn_streamed(moe_streamer* st, const void* x_perm, const int32_t* offsets,
+                            const float* row_w, void* h_ws, float* out, int32_t* status,
+                            void* stream, void* copy_stream) {
+    if (!st) return MOE_ERR_INVALID_ARG;
+    if (st->shape.T == 0) return MOE_OK;
+    if (!x_perm || !offsets || !h_ws || !out || stream == copy_stream) return MOE_ERR_INVALID_ARG;
+    return ffn_streamed(st, x_perm, offsets, row_w, h_ws, out, status, (hipStream_t)stream, (hipStream_t)copy_stream);
+}
+
+int moe_layer_streamed(moe_streamer* st, const void* x, const void* Wr, const float* bias,
+                       float* y, void* workspace, size_t workspace_bytes,
+                       void* stream, void* copy_stream) {
+    if (!st) return MOE_ERR_INVALID_ARG;
+    const moe_shape sh = st->shape;
+    if (sh.T == 0) return MOE_OK;
+    if (!x || !Wr || !y || !workspace || stream == copy_stream) return MOE_ERR_INVALID_ARG;
+    moe_workspace_layout L;
+    layout(sh, &L);
+    if (workspace_bytes < L.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_INVALID_ARG;
+    hipStream_t comp = (hipStream_t)stream, copy = (hipStream_t)copy_stream;
+    return layer_body(sh, x, Wr, bias, y, (char*)workspace, comp,
+                      [&](const void* xp, const int32_t* offsets, const float* row_w, void* h, float* out,
+                          int32_t* status, hipEvent_t) {
+                          return ffn_streamed(st, xp, offsets, row_w, h, out, status, comp, copy);
+                      });
+}
+
+}  // extern "C"

@@ -1,0 +1,77 @@
+// Internal declarations shared by the translation units of the MoE library.
+// Nothing here is part of the C ABI (that is include/moe.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moe.h"
+
+namespace moe {
+
+// Weight tile: 128 output features x 64 reduction elements (see the page
+// format in moe.h).
+constexpr int kTileN = 128;
+constexpr int kTileK = 64;
+
+struct Geom {
+    int esize;            // bytes per element of dtype
+    int64_t tile_bytes;   // kTileN * kTileK * esize
+    int64_t tpp;          // tiles per page
+    int64_t kt_gu;        // H / 64  : k-tiles of the gate/up product
+    int64_t ft;           // F / 128 : f-tiles (each has a W1 and a W3 tile row)
+    int64_t tiles_gu;     // 2 * ft * kt_gu
+    int64_t kt_d;         // F / 64  : k-tiles of the down product
+    int64_t dt;           // H / 128 : d-tiles
+    int64_t tiles_d;      // dt * kt_d
+    int64_t pages_gu, pages_d, ppe;   // pages per expert: GU group, D group, both
+};
+
+int validate_shape(const moe_shape* s);          // MOE_OK or error
+Geom geometry(const moe_shape& s);               // shape must be valid
+
+// thread-local record of the last failing HIP call
+void set_hip_error(hipError_t e);
+#define MOE_HIP_TRY(expr)                               \
+    do {                                                \
+        hipError_t _e = (expr);                         \
+        if (_e != hipSuccess) {                         \
+            ::moe::set_hip_error(_e);                   \
+            return MOE_ERR_HIP;                         \
+        }                                               \
+    } while (0)
+
+int get_opt(int id);
+enum Opt { OPT_FFN_VARIANT = 0, OPT_XCD_REMAP, OPT_PROFILE, OPT_COUNT };
+
+// ---- kernel launchers (each returns MOE_OK or MOE_ERR_HIP) -----------------
+int launch_route(const moe_shape& s, const void* x, const void* Wr, const float* bias,
+                 int32_t* ids, float* w, float* logits, hipStream_t st);
+
+size_t permute_workspace_bytes(const moe_shape& s);
+int launch_permute(const moe_shape& s, const int32_t* ids, const float* topk_w, const void* x,
+                   int32_t* counts, int32_t* offsets, int32_t* row_src, int32_t* row_of,
+                   float* row_w, void* x_perm, void* ws, hipStream_t st);
+
+struct FfnArgs {
+    const void* x_perm;        // dtype [R][H]
+    const int32_t* offsets;    // [E+1]
+    const int32_t* page_table; // [table_experts][ppe]; row used for expert e is (e & table_mask_or_all)
+    const char* pool;
+    int64_t pool_pages;
+    const float* row_w;        // [R] or null
+    void* h;                   // dtype [R][F]
+    float* out;                // [R][H]
+    int32_t* status;           // [4] or null
+    int e_begin, e_end;        // experts processed by this launch
+    int table_row_mod;         // 0: table row = e; n>0: table row = e % n (streamed slots)
+    hipEvent_t mid_event;      // recorded between the gate/up and the down launch when not null
+};
+int launch_expert_ffn(const moe_shape& s, const FfnArgs& a, hipStream_t st);
+int launch_expert_ffn_bf16(const moe_shape& s, const Geom& g, const FfnArgs& a, hipStream_t st);
+int launch_expert_ffn_f32(const moe_shape& s, const Geom& g, const FfnArgs& a, hipStream_t st);
+
+int launch_combine(const moe_shape& s, const float* out, const int32_t* row_of, const float* topk_w,
+                   float* y, hipStream_t st);
+
+}  // namespace moe

@@ -1,0 +1,117 @@
+"""GPU parity at the full workload sizes, in the launch configuration the
+benchmark times (the fused moe_layer call).  The oracle cannot run these sizes
+in full, so: routing and permutation are compared in full (they are cheap), the
+expert FFN and the output on sampled tokens the oracle computes one by one
+(random tokens, the ragged tail rows of every expert, rows of the starved
+expert), plus properties that hold at any size."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2411_11217_amd as M
+from moe_workloads import CONFIGS
+from util import Case, assert_close, check_permutation_valid, compare_routing, say
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_tokens(cfg, ref_pm, ids, n_random=12, seed=0):
+    rng = np.random.default_rng(seed)
+    toks = set(rng.choice(cfg.T, size=min(n_random, cfg.T), replace=False).tolist())
+    toks.update([0, cfg.T - 1])
+    row_src, offsets = ref_pm["row_src"], ref_pm["offsets"]
+    for e in range(cfg.E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if hi > lo:
+            toks.add(int(row_src[hi - 1]) // cfg.k)      # last row of the expert: inside the ragged tail tile
+            toks.add(int(row_src[lo]) // cfg.k)          # first row of the expert
+    return np.array(sorted(toks), dtype=np.int32)
+
+
+def check_full(case: Case, y: torch.Tensor, ws, label: str):
+    cfg = case.cfg
+    t0 = time.time()
+    rt = case.oracle_route()
+    say(f"    oracle route: {time.time() - t0:.1f}s")
+    ids = ws.view("topk_ids").cpu().numpy()
+    w = ws.view("topk_w").cpu().numpy()
+    same = compare_routing(cfg, ids, w, rt, label + " route")
+    pm_gpu = {n: ws.view(n).cpu().numpy() for n in ("counts", "offsets", "row_src", "row_of")}
+    check_permutation_valid(ids, cfg.E, cfg.k, pm_gpu)
+    pm_ref = oracle.permute(ids, cfg.E)                    # the oracle's permutation of the ids the GPU chose
+    for n in pm_ref:
+        assert np.array_equal(pm_gpu[n], pm_ref[n]), n
+    say(f"    counts: {pm_gpu['counts'].tolist()}")
+    assert pm_gpu["counts"].sum() == cfg.T * cfg.k
+    assert ws.view("status").cpu().tolist() == [0, 0, 0, 0]
+    yh = y.cpu().numpy()
+    assert np.isfinite(yh).all()
+
+    toks = sample_tokens(cfg, pm_ref, ids)
+    toks = toks[same[toks]]                                # near-tie tokens are reported above, not compared
+    t0 = time.time()
+    v = case.view
+    flat = (toks[:, None].astype(np.int64) * cfg.k + np.arange(cfg.k)[None, :]).reshape(-1)
+    rows = pm_ref["row_of"][flat]
+    xp = oracle.gather_rows(v["x"], pm_ref["row_src"], cfg.k, cfg.dtype_code)
+    h_ref, o_ref = oracle.expert_ffn(xp, pm_ref["offsets"], v["W1"], v["W3"], v["W2"], cfg.dtype_code, sel=rows)
+    # gate weights of the sampled tokens in the GPU's slot order (same expert set as the oracle's)
+    w_ref = np.zeros((len(toks), cfg.k))
+    for i, t in enumerate(toks):
+        lookup = {int(e): rt["w"][t, s] for s, e in enumerate(rt["ids"][t])}
+        w_ref[i] = [lookup[int(e)] for e in ids[t]]
+    y_ref = oracle.combine(o_ref, np.arange(rows.shape[0], dtype=np.int32), cfg.k, w=w_ref)
+    say(f"    oracle FFN on {len(toks)} sampled tokens ({rows.shape[0]} rows): {time.time() - t0:.1f}s")
+    rows_t = torch.from_numpy(rows.astype(np.int64)).cuda()
+    assert_close(ws.view("x_perm")[rows_t].float().cpu().numpy(),
+                 torch.from_numpy(xp[rows].view(np.int16)).view(torch.bfloat16).float().numpy(), "f32", label + " x_perm rows")
+    assert_close(ws.view("h")[rows_t].float().cpu().numpy(), h_ref, cfg.dtype, label + " h rows")
+    rw = ws.view("row_w")[rows_t].cpu().numpy().astype(np.float64)
+    assert_close(ws.view("out")[rows_t].cpu().numpy(), o_ref * rw[:, None], cfg.dtype, label + " out rows")
+    assert_close(yh[toks], y_ref, cfg.dtype, label + " y (sampled tokens)")
+
+
+@pytest.mark.parametrize("name", ["c2_mixtral8x7b_t256", "c3_mixtral8x7b_t4096"])
+def test_mixtral_8x7b_shapes(name):
+    # the two workloads share the layer shape; they differ in seed and token count
+    cfg = CONFIGS[name]
+    t0 = time.time()
+    case = Case(cfg)
+    say(f"    inputs + pages ready: {time.time() - t0:.1f}s")
+    y, ws = M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev)
+    torch.cuda.synchronize()
+    check_full(case, y, ws, name)
+
+
+def test_mixtral_8x22b_skewed():
+    cfg = CONFIGS["c4_mixtral8x22b_t8192_skew"]
+    t0 = time.time()
+    case = Case(cfg)
+    say(f"    inputs + pages ready: {time.time() - t0:.1f}s")
+    y, ws = M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev, bias=case.bias)
+    torch.cuda.synchronize()
+    share = ws.view("counts").cpu().numpy() / float(cfg.R)
+    assert 0.38 <= share[0] <= 0.42 and 0 < share[7] < 0.02, share
+    check_full(case, y, ws, cfg.name)
+
+
+def test_dbrx_streamed_from_pinned_host():
+    cfg = CONFIGS["c5_dbrx_t16384_streamed"]
+    t0 = time.time()
+    case = Case(cfg, pin_pages=True)
+    say(f"    inputs + pinned pages ready: {time.time() - t0:.1f}s")
+    st = M.Streamer(case.shape, case.pw.pages_host, case.pw.table_host)
+    try:
+        y, ws = M.moe_layer_streamed(st, case.x, case.Wr)
+        torch.cuda.synchronize()
+        check_full(case, y, ws, cfg.name)
+        # the same layer with every page resident gives the same bits
+        case.pw.to_device(keep_host=True)
+        y_res, _ = M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev)
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_res)
+    finally:
+        st.close()
