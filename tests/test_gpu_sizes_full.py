@@ -13,7 +13,7 @@ import torch
 import oracle
 import paper_2411_11217_amd as M
 from moe_workloads import CONFIGS
-from util import Case, assert_close, check_permutation_valid, compare_routing, say
+from util import Case, assert_close, assert_h_close, check_permutation_valid, compare_routing, say
 
 pytestmark = pytest.mark.gpu
 
@@ -68,7 +68,7 @@ def check_full(case: Case, y: torch.Tensor, ws, label: str):
     rows_t = torch.from_numpy(rows.astype(np.int64)).cuda()
     assert_close(ws.view("x_perm")[rows_t].float().cpu().numpy(),
                  torch.from_numpy(xp[rows].view(np.int16)).view(torch.bfloat16).float().numpy(), "f32", label + " x_perm rows")
-    assert_close(ws.view("h")[rows_t].float().cpu().numpy(), h_ref, cfg.dtype, label + " h rows")
+    assert_h_close(ws.view("h")[rows_t].float().cpu().numpy(), h_ref, cfg.dtype, label + " h rows")
     rw = ws.view("row_w")[rows_t].cpu().numpy().astype(np.float64)
     assert_close(ws.view("out")[rows_t].cpu().numpy(), o_ref * rw[:, None], cfg.dtype, label + " out rows")
     assert_close(yh[toks], y_ref, cfg.dtype, label + " y (sampled tokens)")
