@@ -73,9 +73,11 @@ int moe_validate_shape(const moe_shape* s);
  * A.1; the paper fixes neither page size nor content).  The unit is a TILE of
  * 128 output features x 64 reduction elements (16 KiB bf16, 32 KiB f32), stored
  * as 128 rows of 64 elements; inside a row the 16-byte chunk with index c is
- * stored at chunk position c ^ (row & 7) for c < 8 (for f32 rows, which have 16
- * chunks, bit 3 of c is kept), which is the bank-conflict-free image the GEMM
- * kernels copy straight into LDS.  A page holds page_bytes / tile_bytes
+ * stored at chunk position c ^ ((row >> 1) & 7) for c < 8 (for f32 rows, which
+ * have 16 chunks, bit 3 of c is kept).  This is the image the GEMM kernels copy
+ * straight into LDS: with 64 LDS banks two 128-byte rows share a bank row, and
+ * XOR-ing with row/2 makes the 16-lane phases of a 128-bit LDS read of an MFMA
+ * operand (one row per lane, same chunk) touch every bank once.  A page holds page_bytes / tile_bytes
  * consecutive tiles and never spans experts.  Expert e owns
  * pages_gu + pages_d logical pages:
  *   group GU (logical pages 0 .. pages_gu-1): tiles ordered [f/128][w][h/64],

@@ -90,7 +90,7 @@ def library_path() -> str:
 def _lib():
     global _LIB
     if _LIB is None:
-        path = _build.LIB
+        path = os.environ.get("MOE_HIP_LIBRARY", _build.LIB)     # override: an experimental build of the same ABI
         if not os.path.exists(path):
             path = _build.build(force=True)          # raises if hipcc is missing or the build fails
         lib = ctypes.CDLL(path)

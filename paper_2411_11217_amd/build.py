@@ -34,16 +34,19 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
-    """Compile every .hip file and link the shared library.  Returns its path."""
+def build(force: bool = True, verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
+    """Compile every .hip file and link the shared library.  Returns its path.
+
+    ``extra_flags`` / ``out`` build an experimental variant next to the default library."""
     if not force and not is_stale():
         return LIB
-    os.makedirs(BUILD, exist_ok=True)
+    build_dir = BUILD if out == LIB else BUILD + "_" + os.path.basename(out).replace(".", "_")
+    os.makedirs(build_dir, exist_ok=True)
     hipcc = os.environ.get("HIPCC", "hipcc")
 
     def compile_one(src):
-        obj = os.path.join(BUILD, os.path.basename(src)[:-4] + ".o")
-        cmd = [hipcc] + FLAGS + ["-c", src, "-o", obj]
+        obj = os.path.join(build_dir, os.path.basename(src)[:-4] + ".o")
+        cmd = [hipcc] + FLAGS + list(extra_flags) + ["-c", src, "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed for %s:\n%s" % (src, r.stderr[-8000:]))
@@ -53,12 +56,14 @@ def build(force: bool = True, verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(max_workers=min(8, max(1, len(sources())))) as pool:
         objs = list(pool.map(compile_one, sources()))
-    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs,
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + objs,
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr[-8000:])
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
-    print(build(force=True, verbose="-v" in sys.argv))
+    flags = [a for a in sys.argv[1:] if a.startswith("-D")]
+    outs = [a for a in sys.argv[1:] if a.endswith(".so")]
+    print(build(force=True, verbose="-v" in sys.argv, extra_flags=flags, out=outs[0] if outs else LIB))

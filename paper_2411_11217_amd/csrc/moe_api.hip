@@ -14,11 +14,12 @@ void set_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
 
 // ---- options ----------------------------------------------------------------
 static int g_opts[OPT_COUNT] = {
-    /*OPT_FFN_VARIANT*/ 1,   // 0: synchronous single-buffer loop, 1: double-buffered direct-to-LDS loop
+    /*OPT_FFN_VARIANT*/ 1,   // 0: synchronous single-buffer loop, 1: double-buffered loop, 2: double-buffered ping-pong
     /*OPT_XCD_REMAP*/ 1,     // 1: tiles are dealt to the 8 XCDs in contiguous chunks
     /*OPT_PROFILE*/ 0,       // 1: moe_layer records stage events (see moe_profile_read)
+    /*OPT_DEBUG_SAME_TILE*/ 0,   // measurement only: every block reads the operands of tile (0,0) (wrong results)
 };
-static const char* g_opt_names[OPT_COUNT] = {"ffn_variant", "xcd_remap", "profile"};
+static const char* g_opt_names[OPT_COUNT] = {"ffn_variant", "xcd_remap", "profile", "debug_same_tile"};
 int get_opt(int id) { return g_opts[id]; }
 
 int validate_shape(const moe_shape* s) {
@@ -60,7 +61,7 @@ static void copy_tile(char* page_tile, char* dense, int64_t ld, int esize, bool 
         char* prow = page_tile + (int64_t)n * row_bytes;
         char* drow = dense + (int64_t)n * ld * esize;
         for (int c = 0; c < chunks; ++c) {
-            const int pos = (c & ~7) | ((c & 7) ^ (n & 7));
+            const int pos = (c & ~7) | ((c & 7) ^ ((n >> 1) & 7));
             if (to_page) std::memcpy(prow + pos * 16, drow + c * 16, 16);
             else std::memcpy(drow + c * 16, prow + pos * 16, 16);
         }

@@ -31,6 +31,7 @@ struct GemmParams {
     int32_t* status;
     int32_t xcd_remap;
     int32_t variant;
+    int32_t debug_same_tile;
 };
 
 struct TileCoord {
@@ -38,39 +39,82 @@ struct TileCoord {
     bool valid;
 };
 
-// Tile numbers run over the row tiles of a column tile first, then over the
-// column tiles, then over the experts.  With xcd_remap the numbers are dealt to
-// the 8 XCDs (block b runs on XCD b % 8) in contiguous chunks.  The row-tile
-// count of every expert comes from offsets[], so the grid is only an upper bound
-// and surplus blocks leave at once.
+// Tile order.  Row tiles come in two classes: FULL tiles (BM valid rows) and the
+// at most one PARTIAL tile at the end of each expert's segment, which is cheaper
+// because MFMA tiles without valid rows are skipped.  All full tiles are numbered
+// first, the partial ones after them, so the short tiles fill the end of the
+// launch instead of delaying full tiles (longest-first scheduling; blocks are
+// dispatched in block-id order).  Inside a class the numbers run over the row
+// tiles of one column tile first (they share the weight tiles), then over the
+// column tiles, then over the experts.  With xcd_remap each class is dealt to the
+// 8 XCDs (block b runs on XCD b % 8, each with its own L2) in contiguous chunks.
+// The tile counts come from offsets[], so the grid is only an upper bound and
+// surplus blocks leave at once.
+//
+// Every wavefront does the search on its own, one expert per lane (at most 64
+// experts): one load of the segment bounds, prefix sums of the tile counts over
+// the lanes, a ballot to find the expert that holds the tile number.  The result
+// is the same in all lanes.
+__device__ __forceinline__ int lane_prefix_sum(int v, int lane) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int u = __shfl_up(v, d, 64);
+        if (lane >= d) v += u;
+    }
+    return v;
+}
+
 template <int BM>
 __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     TileCoord t{};
     t.valid = false;
-    int total_m = 0;
-    for (int e = p.e_begin; e < p.e_end; ++e) total_m += (p.offsets[e + 1] - p.offsets[e] + BM - 1) / BM;
-    const int total = total_m * p.NT;
+    const int lane = threadIdx.x & 63;
+    const int e_l = p.e_begin + lane;
+    int seg0 = 0, cnt = 0;
+    if (e_l < p.e_end) {
+        seg0 = p.offsets[e_l];
+        cnt = p.offsets[e_l + 1] - seg0;
+    }
+    const int full_l = cnt / BM;                   // full row tiles of my expert
+    const int part_l = (cnt % BM) != 0;            // 0 or 1 partial row tile
+    const int full_incl = lane_prefix_sum(full_l, lane);
+    const int part_incl = lane_prefix_sum(part_l, lane);
+    const int total_full = __builtin_amdgcn_readlane(full_incl, 63) * p.NT;
+    const int total_part = __builtin_amdgcn_readlane(part_incl, 63) * p.NT;
+    // position in the launch order -> (class, number inside the class)
     int L = blockIdx.x;
+    bool partial;
     if (p.xcd_remap) {
-        const int chunk = (total + 7) >> 3;
-        const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-        if (idx >= chunk) return t;
-        L = xcd * chunk + idx;
+        const int chunk_f = (total_full + 7) >> 3, chunk_p = (total_part + 7) >> 3;
+        const int xcd = blockIdx.x & 7;
+        int idx = blockIdx.x >> 3;
+        partial = idx >= chunk_f;
+        if (partial) {
+            idx -= chunk_f;
+            if (idx >= chunk_p) return t;
+            L = xcd * chunk_p + idx;
+        } else {
+            L = xcd * chunk_f + idx;
+        }
+    } else {
+        partial = L >= total_full;
+        if (partial) L -= total_full;
     }
-    if (L >= total) return t;
-    int e = p.e_begin, mtiles = 1;
-    for (; e < p.e_end; ++e) {
-        mtiles = (p.offsets[e + 1] - p.offsets[e] + BM - 1) / BM;
-        const int tiles_e = mtiles * p.NT;
-        if (L < tiles_e) break;
-        L -= tiles_e;
-    }
-    if (e >= p.e_end) return t;   // not reachable when offsets are consistent
-    t.e = e;
+    if (L >= (partial ? total_part : total_full)) return t;
+    const int incl = partial ? part_incl : full_incl;
+    const int mine = partial ? part_l : full_l;
+    const unsigned long long holds = __ballot(L < incl * p.NT);      // lanes of this and later experts
+    const int src = __builtin_amdgcn_readfirstlane(__ffsll((long long)holds) - 1);
+    const int mtiles = __builtin_amdgcn_readfirstlane(__shfl(mine, src, 64));
+    const int before = __builtin_amdgcn_readfirstlane(__shfl(incl - mine, src, 64));
+    const int seg = __builtin_amdgcn_readfirstlane(__shfl(seg0, src, 64));
+    const int rows = __builtin_amdgcn_readfirstlane(__shfl(cnt, src, 64));
+    L -= before * p.NT;
+    t.e = p.e_begin + src;
     t.nt = L / mtiles;
-    t.mt = L - t.nt * mtiles;
-    t.row0 = p.offsets[e] + t.mt * BM;
-    t.rows_here = min(BM, p.offsets[e + 1] - t.row0);
+    t.mt = partial ? rows / BM : L - t.nt * mtiles;
+    t.row0 = seg + t.mt * BM;
+    t.rows_here = min(BM, rows - t.mt * BM);
     t.valid = t.rows_here > 0;
     return t;
 }
@@ -91,7 +135,7 @@ __device__ __forceinline__ const char* tile_address(const GemmParams& p, const i
 // grid size that covers every tile for any routing result
 inline int gemm_grid(int NT, int R, int BM, int n_experts) {
     const int m_tiles_max = R / BM + n_experts;   // >= sum over experts of ceil(rows / BM)
-    return ((NT * m_tiles_max + 7) / 8 + 1) * 8;
+    return ((NT * m_tiles_max + 7) / 8 + 2) * 8;   // each of the two tile classes is rounded up to a multiple of 8
 }
 
 inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const FfnArgs& a) {
@@ -109,6 +153,7 @@ inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const 
     p.status = a.status;
     p.xcd_remap = get_opt(OPT_XCD_REMAP);
     p.variant = get_opt(OPT_FFN_VARIANT);
+    p.debug_same_tile = get_opt(OPT_DEBUG_SAME_TILE);
 }
 
 // parameters of the gate/up launch (K = H, output h[R][F]) and of the down launch

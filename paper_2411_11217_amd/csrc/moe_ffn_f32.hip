@@ -24,10 +24,10 @@ constexpr int kTileBytes = 128 * 64 * 4;             // 32768
 constexpr int kLdsBytes = kABytes + 2 * kTileBytes;  // 82944
 
 // float offset of element (n, k) inside a page tile: 16-byte chunk c = k/4 sits at
-// chunk position (c & 8) | ((c & 7) ^ (n & 7))
+// chunk position (c & 8) | ((c & 7) ^ ((n >> 1) & 7))
 __device__ __forceinline__ int b_elem(int n, int k) {
     const int c = k >> 2;
-    return n * 64 + ((((c & 8) | ((c & 7) ^ (n & 7)))) << 2) + (k & 3);
+    return n * 64 + ((((c & 8) | ((c & 7) ^ ((n >> 1) & 7)))) << 2) + (k & 3);
 }
 
 template <int MODE>

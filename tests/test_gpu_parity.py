@@ -12,6 +12,7 @@ from moe_workloads import CONFIGS, MoEConfig, scaled
 from util import Case, assert_close, assert_h_close, check_permutation_valid, compare_routing, say, shape_of
 
 pytestmark = pytest.mark.gpu
+DEFAULT_VARIANT = 1
 
 C1 = CONFIGS["c1_tiny_f32"]
 # reduced bf16 cases: several row tiles of 256 with ragged tails, several column tiles,
@@ -102,7 +103,7 @@ def test_c1_stagewise_and_layer():
 
 
 @pytest.mark.parametrize("name", list(MED))
-@pytest.mark.parametrize("variant", [1, 0])
+@pytest.mark.parametrize("variant", [2, 1, 0])
 def test_reduced_cases_stagewise_and_layer(name, variant):
     say(f"  case {name} variant {variant}")
     M.set_option("ffn_variant", variant)
@@ -111,7 +112,7 @@ def test_reduced_cases_stagewise_and_layer(name, variant):
         ref = run_stagewise(case)
         run_layer(case, ref)
     finally:
-        M.set_option("ffn_variant", 1)
+        M.set_option("ffn_variant", DEFAULT_VARIANT)
 
 
 def test_xcd_remap_off_gives_identical_bits():
