@@ -71,13 +71,17 @@ int moe_validate_shape(const moe_shape* s);
  *
  * Page format (this library's reading of the paper's weight pages, appendix
  * A.1; the paper fixes neither page size nor content).  The unit is a TILE of
- * 128 output features x 64 reduction elements (16 KiB bf16, 32 KiB f32), stored
- * as 128 rows of 64 elements; inside a row the 16-byte chunk with index c is
- * stored at chunk position c ^ ((row >> 1) & 7) for c < 8 (for f32 rows, which
- * have 16 chunks, bit 3 of c is kept).  This is the image the GEMM kernels copy
- * straight into LDS: with 64 LDS banks two 128-byte rows share a bank row, and
- * XOR-ing with row/2 makes the 16-lane phases of a 128-bit LDS read of an MFMA
- * operand (one row per lane, same chunk) touch every bank once.  A page holds page_bytes / tile_bytes
+ * 128 output features x 64 reduction elements (16 KiB bf16, 32 KiB f32).
+ *   f32:  128 rows of 256 bytes; the 16-byte chunk with index c (0..15) of row n
+ *         is stored at chunk position (c & 8) | ((c & 7) ^ ((n >> 1) & 7)).
+ *   bf16: two half-tiles of 8 KiB, one per 32 reduction elements; half-tile c >> 2
+ *         holds, in row n of 64 bytes, chunk c (0..7) of that row at chunk position
+ *         (c & 3) ^ ((n >> 2) & 3).
+ * These are the images the GEMM kernels copy straight into LDS (the bf16 kernel
+ * consumes 32 reduction elements per pipeline stage).  The LDS has 64 banks of
+ * 4 bytes, a 128-bit LDS read executes in phases of 16 lanes, and the XOR with
+ * the row index makes every phase of a read of an MFMA operand (one row per lane,
+ * same chunk) touch every bank once.  A page holds page_bytes / tile_bytes
  * consecutive tiles and never spans experts.  Expert e owns
  * pages_gu + pages_d logical pages:
  *   group GU (logical pages 0 .. pages_gu-1): tiles ordered [f/128][w][h/64],

@@ -14,12 +14,11 @@ void set_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
 
 // ---- options ----------------------------------------------------------------
 static int g_opts[OPT_COUNT] = {
-    /*OPT_FFN_VARIANT*/ 1,   // 0: synchronous single-buffer loop, 1: double-buffered loop, 2: double-buffered ping-pong
+    /*OPT_FFN_STAGES*/ 4,    // LDS ring depth of the bf16 expert GEMM (3, 4 or 5 stages of 32 KiB)
     /*OPT_XCD_REMAP*/ 1,     // 1: tiles are dealt to the 8 XCDs in contiguous chunks
     /*OPT_PROFILE*/ 0,       // 1: moe_layer records stage events (see moe_profile_read)
-    /*OPT_DEBUG_SAME_TILE*/ 0,   // measurement only: every block reads the operands of tile (0,0) (wrong results)
 };
-static const char* g_opt_names[OPT_COUNT] = {"ffn_variant", "xcd_remap", "profile", "debug_same_tile"};
+static const char* g_opt_names[OPT_COUNT] = {"ffn_stages", "xcd_remap", "profile"};
 int get_opt(int id) { return g_opts[id]; }
 
 int validate_shape(const moe_shape* s) {
@@ -52,18 +51,25 @@ Geom geometry(const moe_shape& s) {
 }
 
 // ---- packer -------------------------------------------------------------------
+// Byte offset inside a page tile of the 16-byte chunk c of row n (the page format of moe.h).
+// bf16: two half-tiles of 128 rows x 64 bytes, chunk c & 3 of half c >> 2 at position
+// (c & 3) ^ ((n >> 2) & 3).  f32: 128 rows x 256 bytes, chunk c at position
+// (c & 8) | ((c & 7) ^ ((n >> 1) & 7)).
+static inline int64_t tile_chunk_offset(int esize, int n, int c) {
+    if (esize == 2) return (int64_t)(c >> 2) * (kTileN * 64) + n * 64 + (((c & 3) ^ ((n >> 2) & 3)) << 4);
+    return (int64_t)n * (kTileK * 4) + (((c & 8) | ((c & 7) ^ ((n >> 1) & 7))) << 4);
+}
+
 // Copies one 128 x 64 tile between a dense row-major matrix (leading dimension
 // ld elements) and its page image.  to_page: dense -> page, else page -> dense.
 static void copy_tile(char* page_tile, char* dense, int64_t ld, int esize, bool to_page) {
-    const int row_bytes = kTileK * esize;
-    const int chunks = row_bytes / 16;
+    const int chunks = kTileK * esize / 16;
     for (int n = 0; n < kTileN; ++n) {
-        char* prow = page_tile + (int64_t)n * row_bytes;
         char* drow = dense + (int64_t)n * ld * esize;
         for (int c = 0; c < chunks; ++c) {
-            const int pos = (c & ~7) | ((c & 7) ^ ((n >> 1) & 7));
-            if (to_page) std::memcpy(prow + pos * 16, drow + c * 16, 16);
-            else std::memcpy(drow + c * 16, prow + pos * 16, 16);
+            char* pc = page_tile + tile_chunk_offset(esize, n, c);
+            if (to_page) std::memcpy(pc, drow + c * 16, 16);
+            else std::memcpy(drow + c * 16, pc, 16);
         }
     }
 }

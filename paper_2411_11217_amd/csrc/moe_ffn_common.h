@@ -30,8 +30,6 @@ struct GemmParams {
     const float* row_w;
     int32_t* status;
     int32_t xcd_remap;
-    int32_t variant;
-    int32_t debug_same_tile;
 };
 
 struct TileCoord {
@@ -152,8 +150,6 @@ inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const 
     p.table_row_mod = a.table_row_mod;
     p.status = a.status;
     p.xcd_remap = get_opt(OPT_XCD_REMAP);
-    p.variant = get_opt(OPT_FFN_VARIANT);
-    p.debug_same_tile = get_opt(OPT_DEBUG_SAME_TILE);
 }
 
 // parameters of the gate/up launch (K = H, output h[R][F]) and of the down launch

@@ -10,7 +10,8 @@
 namespace moe {
 
 // Weight tile: 128 output features x 64 reduction elements (see the page
-// format in moe.h).
+// format in moe.h).  A bf16 tile is stored as two half-tiles of 32 reduction
+// elements each.
 constexpr int kTileN = 128;
 constexpr int kTileK = 64;
 
@@ -42,7 +43,7 @@ void set_hip_error(hipError_t e);
     } while (0)
 
 int get_opt(int id);
-enum Opt { OPT_FFN_VARIANT = 0, OPT_XCD_REMAP, OPT_PROFILE, OPT_DEBUG_SAME_TILE, OPT_COUNT };
+enum Opt { OPT_FFN_STAGES = 0, OPT_XCD_REMAP, OPT_PROFILE, OPT_COUNT };
 
 // ---- kernel launchers (each returns MOE_OK or MOE_ERR_HIP) -----------------
 int launch_route(const moe_shape& s, const void* x, const void* Wr, const float* bias,

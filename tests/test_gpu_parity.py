@@ -12,7 +12,7 @@ from moe_workloads import CONFIGS, MoEConfig, scaled
 from util import Case, assert_close, assert_h_close, check_permutation_valid, compare_routing, say, shape_of
 
 pytestmark = pytest.mark.gpu
-DEFAULT_VARIANT = 1
+DEFAULT_STAGES = 4
 
 C1 = CONFIGS["c1_tiny_f32"]
 # reduced bf16 cases: several row tiles of 256 with ragged tails, several column tiles,
@@ -103,16 +103,16 @@ def test_c1_stagewise_and_layer():
 
 
 @pytest.mark.parametrize("name", list(MED))
-@pytest.mark.parametrize("variant", [2, 1, 0])
-def test_reduced_cases_stagewise_and_layer(name, variant):
-    say(f"  case {name} variant {variant}")
-    M.set_option("ffn_variant", variant)
+@pytest.mark.parametrize("stages", [4, 3, 5])
+def test_reduced_cases_stagewise_and_layer(name, stages):
+    say(f"  case {name} ffn_stages {stages}")
+    M.set_option("ffn_stages", stages)
     try:
         case = Case(MED[name], shuffle_pages=True, extra_pages=3)
         ref = run_stagewise(case)
         run_layer(case, ref)
     finally:
-        M.set_option("ffn_variant", DEFAULT_VARIANT)
+        M.set_option("ffn_stages", DEFAULT_STAGES)
 
 
 def test_xcd_remap_off_gives_identical_bits():

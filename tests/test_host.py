@@ -85,15 +85,22 @@ def test_pack_unpack_round_trip_and_layout(dtype):
     U1, U3, U2 = pw.unpack()
     assert torch.equal(U1, W1) and torch.equal(U3, W3) and torch.equal(U2, W2)
 
-    # documented layout: tile (f/128, w, h/64) of group GU; 16-byte chunk c of row n at position c ^ ((n >> 1) & 7)
+    # documented layout: tile (f/128, w, h/64) of group GU; inside a tile the 16-byte chunk c of row n sits
+    # (f32)  in row n of 256 bytes at position (c & 8) | ((c & 7) ^ ((n >> 1) & 7)),
+    # (bf16) in half-tile c >> 2 (8 KiB each), row n of 64 bytes, at position (c & 3) ^ ((n >> 2) & 3)
     esz = 2 if dtype == "bf16" else 4
+
+    def chunk_offset(n, c):
+        if dtype == "bf16":
+            return (c >> 2) * 8192 + n * 64 + (((c & 3) ^ ((n >> 2) & 3)) << 4)
+        return n * 256 + (((c & 8) | ((c & 7) ^ ((n >> 1) & 7))) << 4)
+
     tb = M.tile_bytes(s)
     tpp = s.page_bytes // tb
     e, ft, w, kt, n, c = 2, 1, 1, 3, 77, 5
     ti = (ft * 2 + w) * (H // 64) + kt
     slot = int(pw.table_host[e, ti // tpp])
-    pos = (c & ~7) | ((c & 7) ^ ((n >> 1) & 7))
-    off = (ti % tpp) * tb + n * 64 * esz + pos * 16
+    off = (ti % tpp) * tb + chunk_offset(n, c)
     got = pw.pages_host[slot, off:off + 16]
     src = W3[e, ft * 128 + n, kt * 64 + c * (16 // esz): kt * 64 + (c + 1) * (16 // esz)].contiguous()
     assert torch.equal(got, src.view(torch.uint8))
@@ -101,8 +108,7 @@ def test_pack_unpack_round_trip_and_layout(dtype):
     dtile, kt2, n, c = 1, 4, 9, 2
     ti = dtile * (F // 64) + kt2
     slot = int(pw.table_host[e, pw.pages_gu + ti // tpp])
-    pos = (c & ~7) | ((c & 7) ^ ((n >> 1) & 7))
-    off = (ti % tpp) * tb + n * 64 * esz + pos * 16
+    off = (ti % tpp) * tb + chunk_offset(n, c)
     src = W2[e, dtile * 128 + n, kt2 * 64 + c * (16 // esz): kt2 * 64 + (c + 1) * (16 // esz)].contiguous()
     assert torch.equal(pw.pages_host[slot, off:off + 16], src.view(torch.uint8))
 
