@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--option", action="append", default=[], help="library option name=value")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="instead of the layer, run a plain device copy of 1 GiB ten times (calibrates the "
+                         "FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc against known traffic)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -51,6 +54,16 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.copy_probe:
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": n, "copy_probe_bytes_written": n, "launches": 10}))
+        return
     cfg = CONFIGS[args.config]
     for o in args.option:
         name, val = o.split("=")

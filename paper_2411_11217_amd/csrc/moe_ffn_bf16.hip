@@ -13,7 +13,8 @@
 // expert boundary; the block finds (expert, row tile, column tile) from the
 // offsets array alone, so the host needs no knowledge of the routing result.
 //
-// Data movement.  512 threads = 8 wavefronts (2 per SIMD).  The reduction runs in
+// Data movement.  256 threads = 4 wavefronts, one per SIMD, each with the full
+// register file (256 accumulator + 256 vector registers).  The reduction runs in
 // HALF-STEPS of 32 elements.  One half-step needs a STAGE of 32 KiB in LDS: 256
 // activation rows x 64 bytes and two weight half-tiles of 128 rows x 64 bytes.  A
 // ring of kStages stages is kept; the stage of half-step k + kStages - 1 is loaded
@@ -36,9 +37,12 @@
 // interleaved: between two MFMAs at most two LDS fetches or one global load are
 // issued.  Scheduling fences pin that order.
 //
-// Wavefront w computes rows (w / 4) * 128 .. +127 and, of the 256 columns, for
-// MODE 0 columns (w % 4) * 32 .. +31 of both tiles, for MODE 1 columns
-// (w % 4) * 64 .. +63: 4 x 2 MFMA tiles of 32 x 32, 128 accumulator registers.
+// Wavefront w computes rows (w / 2) * 128 .. +127 and, of the 256 columns, for
+// MODE 0 columns (w % 2) * 64 .. +63 of both tiles, for MODE 1 columns
+// (w % 2) * 128 .. +127: 4 x 4 MFMA tiles of 32 x 32, 256 accumulator registers.
+// Measured against 8 wavefronts of 128 x 64 each: a 128 x 128 wavefront tile needs
+// 8 LDS fetches per 16 MFMAs instead of 12, a third less LDS traffic; the chip is
+// power limited under this load, the clock rises and the loop runs ~10 % faster.
 #include <mutex>
 #include <type_traits>
 
@@ -55,15 +59,19 @@ typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 constexpr int BM = 256;
-constexpr int kThreads = 512;
+constexpr int kThreads = 256;
+constexpr int kWaves = 4;
 constexpr int kRowB = 64;                    // bytes of one row in a stage (32 bf16)
 constexpr int kStageA = 256 * kRowB;         // activation part of a stage
 constexpr int kStageBytes = 2 * kStageA;     // + two weight half-tiles of 8 KiB
 constexpr int kHalfTile = 128 * kRowB;       // one weight half-tile
-constexpr int kLoadsPerStage = 4;            // global_load_lds instructions per wavefront per stage
+constexpr int kLoadsPerStage = 8;            // global_load_lds instructions per wavefront per stage
 
+// silu(g) * u with the hardware exp2 and reciprocal (1 ulp each): far below the resolution of
+// the bf16 result; an IEEE division would cost a dozen instructions per element
 __device__ __forceinline__ float silu_mul(float g, float u) {
-    return g * __frcp_rn(1.0f + __expf(-g)) * u;
+    const float e = __builtin_amdgcn_exp2f(g * -1.44269504088896340736f);
+    return g * __builtin_amdgcn_rcpf(1.0f + e) * u;
 }
 
 // wait until at most N of my vector-memory loads are outstanding and all my LDS fetches are back
@@ -72,17 +80,32 @@ __device__ __forceinline__ void wait_loads_and_lds() {
     __builtin_amdgcn_s_waitcnt(0x0070 | (N & 15) | ((N >> 4) << 14));
 }
 
+#ifdef MOE_FFN_TIMELINE
+__device__ __forceinline__ long long rows_here_tl(int rows) { return (long long)rows << 8; }
+#endif
+
 template <int MODE, int S>
 __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 2, wn = wave & 3;
+    const int wm = wave >> 1, wn = wave & 1;
 
+#ifdef MOE_FFN_TIMELINE   // experiment builds only: per-block time stamps behind the status words
+    long long* tl = (long long*)(p.status + 4) + ((size_t)blockIdx.x + MODE * 6144) * 8;
+    const long long t_entry = clock64();
+#define MOE_TL(i) do { if (tid == 0) tl[i] = clock64() - t_entry; } while (0)
+#else
+#define MOE_TL(i) ((void)0)
+#endif
     // ---- which tile is mine -------------------------------------------------
     const TileCoord tc = locate_tile<BM>(p);
     if (!tc.valid) return;
+#ifdef MOE_FFN_TIMELINE
+    if (tid == 0) { tl[0] = t_entry; tl[5] = wall_clock64(); tl[7] = 1 + rows_here_tl(tc.rows_here); }
+#endif
+    MOE_TL(1);
     const int e = tc.e, nt = tc.nt, row0 = tc.row0, rows_here = tc.rows_here;
 
     // ---- weight tiles through the page table -------------------------------------
@@ -120,41 +143,43 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     TileWalk w0 = walk_start(pt0 * p.KT), w1 = walk_start(pt1 * p.KT);
 
     // ---- per-lane sources of the activation rows ------------------------------------
-    // load instruction q = i*8 + wave (i = 0, 1) fills LDS rows q*16 .. q*16+15 (1 KiB); lane j
+    // load instruction q = i*4 + wave (i = 0..3) fills LDS rows q*16 .. q*16+15 (1 KiB); lane j
     // holds row q*16 + j/4 at chunk position j%4, i.e. global chunk (j%4) ^ ((row >> 2) & 3)
-    const char* a_src[2];
+    const char* a_src[4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int lrow = (i * 8 + wave) * 16 + (lane >> 2);
+    for (int i = 0; i < 4; ++i) {
+        const int lrow = (i * kWaves + wave) * 16 + (lane >> 2);
         const int r = min(lrow, rows_here - 1);                               // rows past the tail repeat the last row
         const int c = (lane & 3) ^ ((lrow >> 2) & 3);
         a_src[i] = p.A + (int64_t)(row0 + r) * p.lda_bytes + c * 16;
     }
     const int b_lane_off = wave * 1024 + lane * 16;
 
-    // Load instruction i (0, 1: activation rows; 2, 3: weight half-tile 0, 1) of half-step kn
-    // into ring slot `slot`.  After the last instruction of an odd half-step the tile walk moves on.
+    // Load instruction i (0..3: activation rows; 4, 5: weight half-tile 0; 6, 7: weight half-tile 1)
+    // of half-step kn into ring slot `slot`.  After the last instruction of an odd half-step the
+    // tile walk moves on.
     const int KH = 2 * p.KT;
     auto load_part = [&](int slot, int kn, int i) {
         char* st = smem + slot * kStageBytes;
-        if (i < 2) {
-            __builtin_amdgcn_global_load_lds((gptr_t)(a_src[i] + (int64_t)kn * kRowB), (lptr_t)(st + (i * 8 + wave) * 1024), 16, 0, 0);
+        if (i < 4) {
+            __builtin_amdgcn_global_load_lds((gptr_t)(a_src[i] + (int64_t)kn * kRowB), (lptr_t)(st + (i * kWaves + wave) * 1024), 16, 0, 0);
         } else {
-            const TileWalk& w = i == 2 ? w0 : w1;
-            const char* b = w.base + (int64_t)w.within * 16384 + (kn & 1) * kHalfTile + b_lane_off;
-            __builtin_amdgcn_global_load_lds((gptr_t)b, (lptr_t)(st + kStageA + (i - 2) * kHalfTile + wave * 1024), 16, 0, 0);
-            if (i == 3 && (kn & 1) && kn + 1 < KH) {
+            const TileWalk& w = i < 6 ? w0 : w1;
+            const int part = (i & 1) * (kWaves * 1024);                       // first or second 4 KiB of the half-tile
+            const char* b = w.base + (int64_t)w.within * 16384 + (kn & 1) * kHalfTile + part + b_lane_off;
+            __builtin_amdgcn_global_load_lds((gptr_t)b, (lptr_t)(st + kStageA + (i >= 6 ? kHalfTile : 0) + part + wave * 1024), 16, 0, 0);
+            if (i == 7 && (kn & 1) && kn + 1 < KH) {
                 walk_next(w0);
                 walk_next(w1);
             }
         }
     };
 
-    f32x16 acc[4][2];
+    f32x16 acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
@@ -164,25 +189,48 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     const int lane_row = (lane & 31) * kRowB;
     const int frag_off[2] = {lane_row + (c0 << 4), lane_row + ((c0 ^ 2) << 4)};
     const int a_base = wm * 128 * kRowB;
-    const int b_base[2] = {kStageA + ((MODE == 0) ? wn * 32 : wn * 64) * kRowB,
-                           kStageA + ((MODE == 0) ? 128 + wn * 32 : wn * 64 + 32) * kRowB};
+    // B fragment ns (0..3): MODE 0: gate rows wn*64 + {0, 32} of tile 0, then the same up rows of tile 1;
+    //                       MODE 1: rows wn*128 + ns*32 of the 256 rows of both tiles
+    int b_base[4];
+#pragma unroll
+    for (int ns = 0; ns < 4; ++ns)
+        b_base[ns] = kStageA + ((MODE == 0) ? (ns >> 1) * 128 + wn * 64 + (ns & 1) * 32 : wn * 128 + ns * 32) * kRowB;
     // 32-row MFMA tiles of this wavefront that hold at least one valid row
     const int n_ms = max(0, min(4, (rows_here - wm * 128 + 31) >> 5));
 
-    // operand registers: two sets (one per sub-step), each 4 A fragments and 2 B fragments
-    bf16x8 fr[2][6];
+    // operand registers: two sets (one per sub-step), each 4 A fragments and 4 B fragments
+    bf16x8 fr[2][8];
 #pragma unroll
-    for (int i = 0; i < 6; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
         for (int x = 0; x < 8; ++x) fr[1][i][x] = (__bf16)0.f;    // the first rotated MFMA group adds 0 * 0
 
-    auto fetch = [&](const char* st, int ks, int i) {          // i = 0..3: A fragment, 4..5: B fragment
+    auto fetch = [&](const char* st, int ks, int i) {          // i = 0..3: A fragment, 4..7: B fragment
         const int base = i < 4 ? a_base + i * 32 * kRowB : b_base[i - 4];
         fr[ks][i] = *(const bf16x8*)(st + base + frag_off[ks]);
     };
-    auto mfma = [&](int ks, int j, auto full) {                 // j = 0..7: MFMA tile (j / 2, j % 2)
-        if (decltype(full)::value || (j >> 1) < n_ms)
-            acc[j >> 1][j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[ks][j >> 1], fr[ks][4 + (j & 1)], acc[j >> 1][j & 1], 0, 0, 0);
+    auto mfma = [&](int ks, int j, auto full) {                 // j = 0..15: MFMA tile (j / 4, j % 4)
+        if (decltype(full)::value || (j >> 2) < n_ms)
+            acc[j >> 2][j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[ks][j >> 2], fr[ks][4 + (j & 3)], acc[j >> 2][j & 3], 0, 0, 0);
+    };
+    // One group: the 16 MFMAs of operand set `ms_set`, with the 8 LDS fetches of set `fs_set` from
+    // stage `st` behind the first four of them (in the order the next group consumes them) and
+    // four global loads behind MFMAs 5, 7, 9 and 11.
+    auto group = [&](int ms_set, const char* st, int fs_ks, int nslot, int kn, int first_load, auto full, auto loads_c) {
+        constexpr int order[8] = {4, 0, 5, 6, 7, 1, 2, 3};
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            mfma(ms_set, j, full);
+            MOE_FENCE();
+            if (j < 4) {
+                fetch(st, fs_ks, order[2 * j]);
+                fetch(st, fs_ks, order[2 * j + 1]);
+                MOE_FENCE();
+            } else if (decltype(loads_c)::value && j >= 5 && j <= 11 && (j & 1)) {
+                load_part(nslot, kn, first_load + ((j - 5) >> 1));
+                MOE_FENCE();
+            }
+        }
     };
 
     // One half-step.  LOADS: the stage of half-step k + S - 1 is loaded into the slot that
@@ -190,7 +238,6 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     // half-step k must be complete (the younger stages).
     int slot = 0;
     auto half_step = [&](int k, auto full, auto loads_c, auto waitn_c) {
-        constexpr bool LOADS = decltype(loads_c)::value;
         wait_loads_and_lds<decltype(waitn_c)::value>();
         __builtin_amdgcn_s_barrier();      // stage k is complete for everyone; nobody reads stage k-1 any more
         asm volatile("" ::: "memory");
@@ -200,23 +247,9 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         const int kn = k + S - 1;
         MOE_FENCE();
         // group A: MFMAs of (k-1, sub-step 1); fetch (k, sub-step 0); activation-row loads
-        mfma(1, 0, full); MOE_FENCE(); fetch(st, 0, 4); fetch(st, 0, 5); MOE_FENCE();
-        mfma(1, 1, full); MOE_FENCE(); fetch(st, 0, 0); fetch(st, 0, 1); MOE_FENCE();
-        mfma(1, 2, full); MOE_FENCE(); fetch(st, 0, 2); fetch(st, 0, 3); MOE_FENCE();
-        mfma(1, 3, full); MOE_FENCE(); if (LOADS) load_part(nslot, kn, 0); MOE_FENCE();
-        mfma(1, 4, full); MOE_FENCE();
-        mfma(1, 5, full); MOE_FENCE(); if (LOADS) load_part(nslot, kn, 1); MOE_FENCE();
-        mfma(1, 6, full); MOE_FENCE();
-        mfma(1, 7, full); MOE_FENCE();
+        group(1, st, 0, nslot, kn, 0, full, loads_c);
         // group B: MFMAs of (k, sub-step 0); fetch (k, sub-step 1); weight loads
-        mfma(0, 0, full); MOE_FENCE(); fetch(st, 1, 4); fetch(st, 1, 5); MOE_FENCE();
-        mfma(0, 1, full); MOE_FENCE(); fetch(st, 1, 0); fetch(st, 1, 1); MOE_FENCE();
-        mfma(0, 2, full); MOE_FENCE(); fetch(st, 1, 2); fetch(st, 1, 3); MOE_FENCE();
-        mfma(0, 3, full); MOE_FENCE(); if (LOADS) load_part(nslot, kn, 2); MOE_FENCE();
-        mfma(0, 4, full); MOE_FENCE();
-        mfma(0, 5, full); MOE_FENCE(); if (LOADS) load_part(nslot, kn, 3); MOE_FENCE();
-        mfma(0, 6, full); MOE_FENCE();
-        mfma(0, 7, full); MOE_FENCE();
+        group(0, st, 1, nslot, kn, 4, full, loads_c);
         if (++slot == S) slot = 0;
     };
 
@@ -238,45 +271,74 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         // the MFMAs of the last sub-step
         __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) mfma(1, j, full);
+        for (int j = 0; j < 16; ++j) mfma(1, j, full);
     };
+    MOE_TL(2);
     // a row tile whose last rows are missing skips the MFMA tiles that hold no valid row
     if (n_ms == 4) main_loop(std::true_type{});
     else main_loop(std::false_type{});
+    MOE_TL(3);
 
     // ---- epilogue ---------------------------------------------------------------------
     // accumulator register r of lane l in MFMA tile (ms, ns) is the element at
     // row ms*32 + (r/4)*8 + (l/32)*4 + r%4, column l%32 of that 32 x 32 tile
     const int col_l = lane & 31;
     const int a_row_base = wm * 128;
+    const bool full_rows = rows_here == BM;
     if (MODE == 0) {
-        __bf16* h = (__bf16*)p.out;
-        const int f = nt * 128 + wn * 32 + col_l;
+        __bf16* h = (__bf16*)p.out + (int64_t)row0 * p.ldo + nt * 128 + wn * 64 + col_l;
+        auto store_rows = [&](auto full) {
 #pragma unroll
-        for (int ms = 0; ms < 4; ++ms)
+            for (int ms = 0; ms < 4; ++ms)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = a_row_base + ms * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                if (row < rows_here)
-                    h[(int64_t)(row0 + row) * p.ldo + f] = (__bf16)silu_mul(acc[ms][0][r], acc[ms][1][r]);
-            }
-    } else {
-        float* o = (float*)p.out;
+                for (int r = 0; r < 16; ++r) {
+                    const int row = a_row_base + ms * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                    if (decltype(full)::value || row < rows_here) {
 #pragma unroll
-        for (int ms = 0; ms < 4; ++ms)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = a_row_base + ms * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                if (row < rows_here) {
-                    const float wgt = p.row_w ? p.row_w[row0 + row] : 1.0f;
-#pragma unroll
-                    for (int ns = 0; ns < 2; ++ns) {
-                        const int d = nt * 256 + wn * 64 + ns * 32 + col_l;
-                        if (d < p.n_cols) o[(int64_t)(row0 + row) * p.ldo + d] = acc[ms][ns][r] * wgt;
+                        for (int ns = 0; ns < 2; ++ns)
+                            h[(int64_t)row * p.ldo + ns * 32] = (__bf16)silu_mul(acc[ms][ns][r], acc[ms][ns + 2][r]);
                     }
                 }
-            }
+        };
+        if (full_rows) store_rows(std::true_type{});
+        else store_rows(std::false_type{});
+    } else {
+        // the 256 row weights of the tile go through LDS (free now): one load per thread instead of
+        // one dependent global load per accumulator row
+        float* sw = (float*)smem;
+        __syncthreads();                       // every wavefront has left the main loop
+        sw[tid] = (p.row_w && tid < rows_here) ? p.row_w[row0 + tid] : 1.0f;
+        __syncthreads();
+        const int d0 = nt * 256 + wn * 128;    // n_cols is a multiple of 128: a wavefront's columns are all valid or all not
+        if (d0 < p.n_cols) {
+            float* o = (float*)p.out + (int64_t)row0 * p.ldo + d0 + col_l;
+            auto store_rows = [&](auto full) {
+#pragma unroll
+                for (int ms = 0; ms < 4; ++ms)
+#pragma unroll
+                    for (int rq = 0; rq < 4; ++rq) {
+                        const int rowq = a_row_base + ms * 32 + rq * 8 + (lane >> 5) * 4;      // 4 consecutive rows
+                        const float4 wq = *(const float4*)(sw + rowq);
+                        const float w4[4] = {wq.x, wq.y, wq.z, wq.w};
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int row = rowq + i;
+                            if (decltype(full)::value || row < rows_here) {
+#pragma unroll
+                                for (int ns = 0; ns < 4; ++ns)
+                                    o[(int64_t)row * p.ldo + ns * 32] = acc[ms][ns][rq * 4 + i] * w4[i];
+                            }
+                        }
+                    }
+            };
+            if (full_rows) store_rows(std::true_type{});
+            else store_rows(std::false_type{});
+        }
     }
+    MOE_TL(4);
+#ifdef MOE_FFN_TIMELINE
+    if (tid == 0) tl[6] = wall_clock64() - tl[5];
+#endif
     if (bad && tid == 0 && p.status) atomicOr(p.status, 1);
 }
 
