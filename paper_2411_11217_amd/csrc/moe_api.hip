@@ -17,8 +17,9 @@ static int g_opts[OPT_COUNT] = {
     /*OPT_FFN_STAGES*/ 4,    // LDS ring depth of the bf16 expert GEMM (3, 4 or 5 stages of 32 KiB)
     /*OPT_XCD_REMAP*/ 1,     // 1: tiles are dealt to the 8 XCDs in contiguous chunks
     /*OPT_PROFILE*/ 0,       // 1: moe_layer records stage events (see moe_profile_read)
+    /*OPT_TILE_ORDER*/ 1,    // 0: partial row tiles after all full ones; 1: next to the full row tiles of their column tile
 };
-static const char* g_opt_names[OPT_COUNT] = {"ffn_stages", "xcd_remap", "profile"};
+static const char* g_opt_names[OPT_COUNT] = {"ffn_stages", "xcd_remap", "profile", "tile_order"};
 int get_opt(int id) { return g_opts[id]; }
 
 int validate_shape(const moe_shape* s) {

@@ -30,6 +30,7 @@ struct GemmParams {
     const float* row_w;
     int32_t* status;
     int32_t xcd_remap;
+    int32_t tile_order;
 };
 
 struct TileCoord {
@@ -37,17 +38,18 @@ struct TileCoord {
     bool valid;
 };
 
-// Tile order.  Row tiles come in two classes: FULL tiles (BM valid rows) and the
-// at most one PARTIAL tile at the end of each expert's segment, which is cheaper
-// because MFMA tiles without valid rows are skipped.  All full tiles are numbered
-// first, the partial ones after them, so the short tiles fill the end of the
-// launch instead of delaying full tiles (longest-first scheduling; blocks are
-// dispatched in block-id order).  Inside a class the numbers run over the row
-// tiles of one column tile first (they share the weight tiles), then over the
-// column tiles, then over the experts.  With xcd_remap each class is dealt to the
-// 8 XCDs (block b runs on XCD b % 8, each with its own L2) in contiguous chunks.
-// The tile counts come from offsets[], so the grid is only an upper bound and
-// surplus blocks leave at once.
+// Tile order.  Numbers run over the row tiles of one column tile first (they share the
+// weight tiles), then over the column tiles, then over the experts, and with xcd_remap
+// they are dealt to the 8 XCDs (block b runs on XCD b % 8, each with its own L2) in
+// contiguous chunks, so that the blocks an XCD runs at the same time are a few row tiles
+// times a few column tiles of one expert.  The at most one PARTIAL row tile at the end
+// of an expert's segment is cheaper than a full one (MFMA tiles without valid rows are
+// skipped).  tile_order 1 (default) numbers it right after the full row tiles of its
+// column tile, so that it finds the weight tiles in L2; tile_order 0 numbers all partial
+// tiles after all full ones (longest first), which fills the end of the launch better but
+// was measured to read every weight tile from memory a second time (+26 % L2 misses,
+// +5 % time on the Mixtral-8x7B-shaped workload).  The tile counts come from offsets[],
+// so the grid is only an upper bound and surplus blocks leave at once.
 //
 // Every wavefront does the search on its own, one expert per lane (at most 64
 // experts): one load of the segment bounds, prefix sums of the tile counts over
@@ -73,8 +75,10 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
         seg0 = p.offsets[e_l];
         cnt = p.offsets[e_l + 1] - seg0;
     }
-    const int full_l = cnt / BM;                   // full row tiles of my expert
-    const int part_l = (cnt % BM) != 0;            // 0 or 1 partial row tile
+    // tile_order 0: partial row tiles form a class of their own; 1: one class, the partial
+    // row tile of an expert is numbered right after its full row tiles
+    const int full_l = p.tile_order ? (cnt + BM - 1) / BM : cnt / BM;   // row tiles of my expert in the first class
+    const int part_l = p.tile_order ? 0 : (cnt % BM) != 0;              // 0 or 1 partial row tile
     const int full_incl = lane_prefix_sum(full_l, lane);
     const int part_incl = lane_prefix_sum(part_l, lane);
     const int total_full = __builtin_amdgcn_readlane(full_incl, 63) * p.NT;
@@ -150,6 +154,7 @@ inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const 
     p.table_row_mod = a.table_row_mod;
     p.status = a.status;
     p.xcd_remap = get_opt(OPT_XCD_REMAP);
+    p.tile_order = get_opt(OPT_TILE_ORDER);
 }
 
 // parameters of the gate/up launch (K = H, output h[R][F]) and of the down launch

@@ -115,14 +115,16 @@ def test_reduced_cases_stagewise_and_layer(name, stages):
         M.set_option("ffn_stages", DEFAULT_STAGES)
 
 
-def test_xcd_remap_off_gives_identical_bits():
+@pytest.mark.parametrize("option,default", [("xcd_remap", 1), ("tile_order", 1)])
+def test_tile_numbering_options_give_identical_bits(option, default):
+    # which block computes which tile does not change any arithmetic
     case = Case(MED["bf16_top2_of_4"])
     y1, _ = M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev)
-    M.set_option("xcd_remap", 0)
+    M.set_option(option, 1 - default)
     try:
         y0, _ = M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev)
     finally:
-        M.set_option("xcd_remap", 1)
+        M.set_option(option, default)
     assert torch.equal(y0, y1)
 
 
