@@ -61,11 +61,11 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 constexpr int BM = 256;
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
+constexpr int kComputeUnits = 256;           // MI355X
 constexpr int kRowB = 64;                    // bytes of one row in a stage (32 bf16)
 constexpr int kStageA = 256 * kRowB;         // activation part of a stage
 constexpr int kStageBytes = 2 * kStageA;     // + two weight half-tiles of 8 KiB
 constexpr int kHalfTile = 128 * kRowB;       // one weight half-tile
-constexpr int kLoadsPerStage = 8;            // global_load_lds instructions per wavefront per stage
 
 // silu(g) * u with the hardware exp2 and reciprocal (1 ulp each): far below the resolution of
 // the bf16 result; an IEEE division would cost a dozen instructions per element
@@ -84,8 +84,16 @@ __device__ __forceinline__ void wait_loads_and_lds() {
 __device__ __forceinline__ long long rows_here_tl(int rows) { return (long long)rows << 8; }
 #endif
 
-template <int MODE, int S>
+// NB: page tiles per block along the columns.  2: the 256-column block described above.  1 (MODE 1
+// only): 256 rows x 128 columns, wavefront tile 128 x 64, for launches with too few 256-wide tiles
+// to occupy the chip (few rows per expert: the launch is bound by streaming the weights, and more
+// blocks stream more).
+template <int MODE, int S, int NB>
 __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
+    static_assert(NB == 2 || (NB == 1 && MODE == 1), "gate/up needs the W1 and the W3 tile");
+    constexpr int NS = 2 * NB;                   // 32-column MFMA tiles (B fragments) per wavefront
+    constexpr int NMF = 4 * NS;                  // MFMAs per wavefront per 16-wide sub-step
+    constexpr int kLoadsPerStage = 4 + 2 * NB;   // global_load_lds instructions per wavefront per stage
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -110,8 +118,8 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
 
     // ---- weight tiles through the page table -------------------------------------
     const int32_t* trow = p.table + (size_t)(p.table_row_mod ? e % p.table_row_mod : e) * p.ppe + p.group_base;
-    const int pt0 = nt * 2;
-    const int pt1 = (pt0 + 1 < p.n_page_tiles) ? pt0 + 1 : pt0;   // odd tile count: the second half is masked
+    const int pt0 = nt * NB;
+    const int pt1 = (pt0 + 1 < p.n_page_tiles) ? pt0 + 1 : pt0;   // odd tile count: the second half is masked (NB = 2)
     int bad = 0;
     auto page_addr = [&](int page) -> const char* {
         int slot = __builtin_amdgcn_readfirstlane(trow[page]);
@@ -168,18 +176,18 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
             const int part = (i & 1) * (kWaves * 1024);                       // first or second 4 KiB of the half-tile
             const char* b = w.base + (int64_t)w.within * 16384 + (kn & 1) * kHalfTile + part + b_lane_off;
             __builtin_amdgcn_global_load_lds((gptr_t)b, (lptr_t)(st + kStageA + (i >= 6 ? kHalfTile : 0) + part + wave * 1024), 16, 0, 0);
-            if (i == 7 && (kn & 1) && kn + 1 < KH) {
+            if (i == kLoadsPerStage - 1 && (kn & 1) && kn + 1 < KH) {
                 walk_next(w0);
-                walk_next(w1);
+                if (NB == 2) walk_next(w1);
             }
         }
     };
 
-    f32x16 acc[4][4];
+    f32x16 acc[4][NS];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NS; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
@@ -189,46 +197,51 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     const int lane_row = (lane & 31) * kRowB;
     const int frag_off[2] = {lane_row + (c0 << 4), lane_row + ((c0 ^ 2) << 4)};
     const int a_base = wm * 128 * kRowB;
-    // B fragment ns (0..3): MODE 0: gate rows wn*64 + {0, 32} of tile 0, then the same up rows of tile 1;
-    //                       MODE 1: rows wn*128 + ns*32 of the 256 rows of both tiles
-    int b_base[4];
+    // B fragment ns: MODE 0: gate rows wn*64 + {0, 32} of tile 0, then the same up rows of tile 1;
+    //                MODE 1: rows wn*(32*NS) + ns*32 of the 128*NB rows of the block's tiles
+    int b_base[NS];
 #pragma unroll
-    for (int ns = 0; ns < 4; ++ns)
-        b_base[ns] = kStageA + ((MODE == 0) ? (ns >> 1) * 128 + wn * 64 + (ns & 1) * 32 : wn * 128 + ns * 32) * kRowB;
+    for (int ns = 0; ns < NS; ++ns)
+        b_base[ns] = kStageA + ((MODE == 0) ? (ns >> 1) * 128 + wn * 64 + (ns & 1) * 32 : wn * (32 * NS) + ns * 32) * kRowB;
     // 32-row MFMA tiles of this wavefront that hold at least one valid row
     const int n_ms = max(0, min(4, (rows_here - wm * 128 + 31) >> 5));
 
-    // operand registers: two sets (one per sub-step), each 4 A fragments and 4 B fragments
-    bf16x8 fr[2][8];
+    // operand registers: two sets (one per sub-step), each 4 A fragments and NS B fragments
+    bf16x8 fr[2][4 + NS];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 4 + NS; ++i)
 #pragma unroll
         for (int x = 0; x < 8; ++x) fr[1][i][x] = (__bf16)0.f;    // the first rotated MFMA group adds 0 * 0
 
-    auto fetch = [&](const char* st, int ks, int i) {          // i = 0..3: A fragment, 4..7: B fragment
+    auto fetch = [&](const char* st, int ks, int i) {          // i = 0..3: A fragment, 4..: B fragment
         const int base = i < 4 ? a_base + i * 32 * kRowB : b_base[i - 4];
         fr[ks][i] = *(const bf16x8*)(st + base + frag_off[ks]);
     };
-    auto mfma = [&](int ks, int j, auto full) {                 // j = 0..15: MFMA tile (j / 4, j % 4)
-        if (decltype(full)::value || (j >> 2) < n_ms)
-            acc[j >> 2][j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[ks][j >> 2], fr[ks][4 + (j & 3)], acc[j >> 2][j & 3], 0, 0, 0);
+    auto mfma = [&](int ks, int j, auto full) {                 // j = 0..NMF-1: MFMA tile (j / NS, j % NS)
+        if (decltype(full)::value || (j / NS) < n_ms)
+            acc[j / NS][j % NS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[ks][j / NS], fr[ks][4 + (j % NS)], acc[j / NS][j % NS], 0, 0, 0);
     };
-    // One group: the 16 MFMAs of operand set `ms_set`, with the 8 LDS fetches of set `fs_set` from
-    // stage `st` behind the first four of them (in the order the next group consumes them) and
-    // four global loads behind MFMAs 5, 7, 9 and 11.
-    auto group = [&](int ms_set, const char* st, int fs_ks, int nslot, int kn, int first_load, auto full, auto loads_c) {
-        constexpr int order[8] = {4, 0, 5, 6, 7, 1, 2, 3};
+    // One group: the NMF MFMAs of operand set `ms_set`, with the LDS fetches of set `fs_ks` from
+    // stage `st` behind the first few of them, two at a time, in the order the next group consumes
+    // them, and then `n_loads` global loads, one behind an MFMA (NB = 2: behind every second one).
+    auto group = [&](int ms_set, const char* st, int fs_ks, int nslot, int kn, int first_load, int n_loads, auto full, auto loads_c) {
+        constexpr int order2[8] = {4, 0, 5, 6, 7, 1, 2, 3};
+        constexpr int order1[6] = {4, 0, 5, 1, 2, 3};
+        constexpr int NR2 = (4 + NS) / 2;        // MFMAs that have fetches behind them
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
+        for (int j = 0; j < NMF; ++j) {
             mfma(ms_set, j, full);
             MOE_FENCE();
-            if (j < 4) {
-                fetch(st, fs_ks, order[2 * j]);
-                fetch(st, fs_ks, order[2 * j + 1]);
+            if (j < NR2) {
+                fetch(st, fs_ks, NB == 2 ? order2[2 * j] : order1[2 * j]);
+                fetch(st, fs_ks, NB == 2 ? order2[2 * j + 1] : order1[2 * j + 1]);
                 MOE_FENCE();
-            } else if (decltype(loads_c)::value && j >= 5 && j <= 11 && (j & 1)) {
-                load_part(nslot, kn, first_load + ((j - 5) >> 1));
-                MOE_FENCE();
+            } else if (decltype(loads_c)::value) {
+                const int li = NB == 2 ? (((j - NR2) & 1) ? (j - NR2 - 1) / 2 : -1) : j - NR2;
+                if (li >= 0 && li < n_loads) {
+                    load_part(nslot, kn, first_load + li);
+                    MOE_FENCE();
+                }
             }
         }
     };
@@ -247,9 +260,9 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         const int kn = k + S - 1;
         MOE_FENCE();
         // group A: MFMAs of (k-1, sub-step 1); fetch (k, sub-step 0); activation-row loads
-        group(1, st, 0, nslot, kn, 0, full, loads_c);
+        group(1, st, 0, nslot, kn, 0, 4, full, loads_c);
         // group B: MFMAs of (k, sub-step 0); fetch (k, sub-step 1); weight loads
-        group(0, st, 1, nslot, kn, 4, full, loads_c);
+        group(0, st, 1, nslot, kn, 4, 2 * NB, full, loads_c);
         if (++slot == S) slot = 0;
     };
 
@@ -271,7 +284,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         // the MFMAs of the last sub-step
         __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) mfma(1, j, full);
+        for (int j = 0; j < NMF; ++j) mfma(1, j, full);
     };
     MOE_TL(2);
     // a row tile whose last rows are missing skips the MFMA tiles that hold no valid row
@@ -309,7 +322,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         __syncthreads();                       // every wavefront has left the main loop
         sw[tid] = (p.row_w && tid < rows_here) ? p.row_w[row0 + tid] : 1.0f;
         __syncthreads();
-        const int d0 = nt * 256 + wn * 128;    // n_cols is a multiple of 128: a wavefront's columns are all valid or all not
+        const int d0 = nt * (128 * NB) + wn * (32 * NS);   // n_cols is a multiple of 128: with NB = 2 a wavefront's columns are all valid or all not
         if (d0 < p.n_cols) {
             float* o = (float*)p.out + (int64_t)row0 * p.ldo + d0 + col_l;
             auto store_rows = [&](auto full) {
@@ -325,7 +338,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                             const int row = rowq + i;
                             if (decltype(full)::value || row < rows_here) {
 #pragma unroll
-                                for (int ns = 0; ns < 4; ++ns)
+                                for (int ns = 0; ns < NS; ++ns)
                                     o[(int64_t)row * p.ldo + ns * 32] = acc[ms][ns][rq * 4 + i] * w4[i];
                             }
                         }
@@ -342,26 +355,26 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     if (bad && tid == 0 && p.status) atomicOr(p.status, 1);
 }
 
-template <int MODE, int S>
+template <int MODE, int S, int NB>
 int launch_mode(const GemmParams& p, int grid, hipStream_t st) {
     constexpr int lds = S * kStageBytes;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {
-        attr_err = hipFuncSetAttribute((const void*)ffn_gemm_bf16<MODE, S>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr_err = hipFuncSetAttribute((const void*)ffn_gemm_bf16<MODE, S, NB>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     });
     MOE_HIP_TRY(attr_err);
-    hipLaunchKernelGGL((ffn_gemm_bf16<MODE, S>), dim3(grid), dim3(kThreads), lds, st, p);
+    hipLaunchKernelGGL((ffn_gemm_bf16<MODE, S, NB>), dim3(grid), dim3(kThreads), lds, st, p);
     MOE_HIP_TRY(hipGetLastError());
     return MOE_OK;
 }
 
-template <int MODE>
+template <int MODE, int NB>
 int launch_stages(const GemmParams& p, int grid, hipStream_t st) {
     switch (get_opt(OPT_FFN_STAGES)) {
-        case 3: return launch_mode<MODE, 3>(p, grid, st);
-        case 5: return launch_mode<MODE, 5>(p, grid, st);
-        default: return launch_mode<MODE, 4>(p, grid, st);
+        case 3: return launch_mode<MODE, 3, NB>(p, grid, st);
+        case 5: return launch_mode<MODE, 5, NB>(p, grid, st);
+        default: return launch_mode<MODE, 4, NB>(p, grid, st);
     }
 }
 
@@ -369,14 +382,24 @@ int launch_stages(const GemmParams& p, int grid, hipStream_t st) {
 
 int launch_expert_ffn_bf16(const moe_shape& s, const Geom& g, const FfnArgs& a, hipStream_t st) {
     const int R = s.T * s.k;
+    const int n_exp = a.e_end - a.e_begin;
     GemmParams p{};
     fill_common(p, s, g, a);
     fill_gate_up(p, s, g, a);
-    int rc = launch_stages<0>(p, gemm_grid(p.NT, R, BM, a.e_end - a.e_begin), st);
+    int rc = launch_stages<0, 2>(p, gemm_grid(p.NT, R, BM, n_exp), st);
     if (rc != MOE_OK) return rc;
     if (a.mid_event) MOE_HIP_TRY(hipEventRecord(a.mid_event, st));
     fill_down(p, s, g, a);
-    return launch_stages<1>(p, gemm_grid(p.NT, R, BM, a.e_end - a.e_begin), st);
+    // Down projection with few row tiles: 256-wide column tiles would leave compute units without a
+    // block (the routing result is not known here, R / BM + experts bounds the row tiles), so the
+    // columns are cut into 128-wide tiles instead.  down_cols: 0 = this rule, 1 / 2 = force NB.
+    const int opt = get_opt(OPT_DOWN_COLS);
+    const bool narrow = opt == 1 || (opt == 0 && (int64_t)(R / BM + n_exp) * p.NT < 2 * kComputeUnits);
+    if (narrow) {
+        p.NT = (int32_t)g.dt;
+        return launch_stages<1, 1>(p, gemm_grid(p.NT, R, BM, n_exp), st);
+    }
+    return launch_stages<1, 2>(p, gemm_grid(p.NT, R, BM, n_exp), st);
 }
 
 }  // namespace moe

@@ -103,16 +103,19 @@ def test_c1_stagewise_and_layer():
 
 
 @pytest.mark.parametrize("name", list(MED))
-@pytest.mark.parametrize("stages", [4, 3, 5])
-def test_reduced_cases_stagewise_and_layer(name, stages):
-    say(f"  case {name} ffn_stages {stages}")
+@pytest.mark.parametrize("stages,down_cols", [(4, 2), (4, 1), (3, 0), (5, 0)])
+def test_reduced_cases_stagewise_and_layer(name, stages, down_cols):
+    # ring depth of the GEMM pipeline; 256- and 128-wide column tiles of the down projection (0: by grid size)
+    say(f"  case {name} ffn_stages {stages} down_cols {down_cols}")
     M.set_option("ffn_stages", stages)
+    M.set_option("down_cols", down_cols)
     try:
         case = Case(MED[name], shuffle_pages=True, extra_pages=3)
         ref = run_stagewise(case)
         run_layer(case, ref)
     finally:
         M.set_option("ffn_stages", DEFAULT_STAGES)
+        M.set_option("down_cols", 0)
 
 
 @pytest.mark.parametrize("option,default", [("xcd_remap", 1), ("tile_order", 1)])
