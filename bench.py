@@ -31,10 +31,10 @@ MEASURED_TRAFFIC = {"c3_mixtral8x7b_t4096": 3.784e9}
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="c3_mixtral8x7b_t4096")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=192)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--option", action="append", default=[], help="library option name=value")
     ap.add_argument("--copy-probe", action="store_true",
@@ -122,8 +122,15 @@ def main():
     extra = {}
     if stages:
         t_ffn = (stages["gemm_gate_up"] + stages["gemm_down"]) * 1e-3
+        R, H, F, T, E, b = cfg.R, cfg.H, cfg.F, cfg.T, cfg.E, (2 if cfg.dtype == "bf16" else 4)
+        alg_bytes = {   # algorithmic HBM bytes of the copy-like stages
+            "route": T * H * b + E * H * b + 8 * R,
+            "permute": T * H * b + R * H * b + 12 * R,
+            "combine": 4 * R * H + 4 * R + 4 * T * H,
+        }
         extra = {
             "stage_ms": {k: round(v, 4) for k, v in stages.items()},
+            "stage_hbm_gbs": {k: round(v / (stages[k] * 1e-3) / 1e9, 1) for k, v in alg_bytes.items()},
             "expert_gemms_tflops": round(flops_ffn / t_ffn / 1e12, 2),
             "expert_gemms_frac_of_bf16_peak": round(flops_ffn / t_ffn / 1e12 / PEAK_BF16_TFLOPS, 4),
             "layer_tflops": round((flops_ffn + cfg.router_flops) / (ms_per_step * 1e-3) / 1e12, 2),
@@ -156,6 +163,10 @@ def main():
                    "page_bytes": cfg.page_bytes, "weights": "pinned host, streamed" if cfg.streamed else "resident in HBM"},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
     }
+    if streamer is not None:
+        link_bytes = pw.pages_host.numel() * pw.pages_host.element_size()
+        extra["host_link"] = {"bytes_per_step": link_bytes, "gbs": round(link_bytes / (ms_per_step * 1e-3) / 1e9, 2),
+                              "note": "every weight page crosses the host link once per step; the step is bound by it"}
     out.update(extra)
     print(json.dumps(out), flush=True)
     if streamer is not None:
