@@ -199,6 +199,54 @@ int moe_layer_streamed(moe_streamer* st, const void* x, const void* Wr, const fl
                        float* y, void* workspace, size_t workspace_bytes,
                        void* stream, void* copy_stream);
 
+/* ------------------------------------------------------------------ weight paging over several layers
+ *
+ * The I/O side of the paper's pipeline (section 4.1, "Weights Paging and Data
+ * Transfer Scheduling", and Algorithm 1; double-buffered weight region of
+ * appendix A.1; resident fraction r_w of section 4.2) for a stack of n_layers
+ * MoE layers of one shape and n micro-batches of shape.T tokens per layer:
+ *   - the first resident_pages_per_expert logical pages of every expert of every
+ *     layer stay in the device pool for good (r_w = that number / pages per expert);
+ *   - the other pages of layer l+1 are copied host -> device on `copy_stream`
+ *     while the n micro-batches of layer l are computed on `stream`, cut into n
+ *     chunks of whole pages (one chunk per micro-batch), into the half of a double
+ *     buffer that layer l-1 has finished with;
+ *   - the hidden states of micro-batch j (the paper's transfer D2) are copied host
+ *     -> device on the same copy stream BETWEEN the weight chunks, so a small
+ *     transfer never queues behind more than one chunk of weights.
+ * Layers are taken cyclically: during the last layer the first layer's pages are
+ * fetched for the next call (the next decode step); only the very first call
+ * waits for a layer's pages with nothing to overlap.  Every y is bit-identical
+ * to moe_layer with all pages resident.
+ *
+ * Device pool layout (pool_pages from moe_pipeline_pool_pages):
+ *   n_layers * E * resident pages, then 2 * E * (pages_per_expert - resident) pages.
+ */
+typedef struct moe_pipeline moe_pipeline;
+
+int moe_pipeline_pool_pages(const moe_shape* s, int32_t n_layers, int32_t resident_pages_per_expert,
+                            int64_t* pool_pages);
+/* host_pages[l]: pinned host, host_pool_pages[l] * page_bytes; host_page_tables[l]:
+ * host int32[E][pages_per_expert] (copied); device_pool: device, device_pool_pages *
+ * page_bytes; device_tables: device int32[n_layers][2][E][pages_per_expert], filled
+ * here.  Copies the resident pages synchronously and creates HIP events: not a hot
+ * call.  The host page arrays must stay valid until moe_pipeline_destroy. */
+int moe_pipeline_create(const moe_shape* s, int32_t n_layers, int32_t max_micro_batches,
+                        const void* const* host_pages, const int64_t* host_pool_pages,
+                        const int32_t* const* host_page_tables, int32_t resident_pages_per_expert,
+                        void* device_pool, int64_t device_pool_pages, int32_t* device_tables,
+                        moe_pipeline** out);
+int moe_pipeline_destroy(moe_pipeline* p);
+/* One pass over all layers.  x_host[l * n_micro + j]: pinned host dtype[T][H], the
+ * input of layer l for micro-batch j; x_dev: device staging, dtype[n_micro][T][H];
+ * Wr[l]: device dtype[E][H]; bias: NULL or [n_layers] of device float[E] / NULL;
+ * y[l * n_micro + j]: device float[T][H] (entries may alias each other if the caller
+ * does not need every result).  workspace as for moe_layer.  Enqueues only; if a
+ * call fails part way the pipeline must be destroyed. */
+int moe_pipeline_run(moe_pipeline* p, int32_t n_micro, const void* const* x_host, void* x_dev,
+                     const void* const* Wr, const float* const* bias, float* const* y,
+                     void* workspace, size_t workspace_bytes, void* stream, void* copy_stream);
+
 /* ------------------------------------------------------------------ tuning knobs
  * Named integer options for experiments (kernel variants, tile order); unknown
  * names give MOE_ERR_INVALID_ARG.  Defaults are the measured best. */

@@ -1,14 +1,14 @@
 """MI355X (gfx950) MoE-layer library: Python binding of the C ABI in include/moe.h.
 
 The five calls of the layer -- moe_route, moe_permute, moe_expert_ffn,
-moe_combine and the fused moe_layer -- plus the page packer and the page
-streamer.  All compute runs in the HIP library (libmoe_hip.so, built in-tree by
+moe_combine and the fused moe_layer -- plus the page packer, the page
+streamer and the multi-layer weight-paging pipeline.  All compute runs in the HIP library (libmoe_hip.so, built in-tree by
 ``paper_2411_11217_amd.build``); there is no CPU or PyTorch fallback.
 """
 from .binding import (  # noqa: F401
-    DTYPE_BF16, DTYPE_F32, EXPORTED_SYMBOLS, MAX_EXPERTS, MoEError, MoEShape, Streamer, Workspace,
+    DTYPE_BF16, DTYPE_F32, EXPORTED_SYMBOLS, MAX_EXPERTS, MoEError, MoEShape, Pipeline, Streamer, Workspace,
     get_option, library_path, make_shape, moe_combine, moe_expert_ffn, moe_expert_ffn_streamed, moe_layer,
-    moe_layer_streamed, moe_permute, moe_route, pack_weights, page_table_validate, pages_required, profile_read, set_option,
+    moe_layer_streamed, moe_permute, moe_route, pack_weights, page_table_validate, pages_required, pipeline_pool_pages, profile_read, set_option,
     tile_bytes, unpack_weights, validate_shape, workspace_layout,
 )
 from .paged import PagedWeights  # noqa: F401

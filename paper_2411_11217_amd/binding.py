@@ -74,6 +74,10 @@ _SIGNATURES = {
     "moe_stream_destroy": (ctypes.c_int, [_vp]),
     "moe_expert_ffn_streamed": (ctypes.c_int, [_vp] * 9),
     "moe_layer_streamed": (ctypes.c_int, [_vp] * 6 + [_sz, _vp, _vp]),
+    "moe_pipeline_pool_pages": (ctypes.c_int, [_vp, ctypes.c_int32, ctypes.c_int32, _vp]),
+    "moe_pipeline_create": (ctypes.c_int, [_vp, ctypes.c_int32, ctypes.c_int32, _vp, _vp, _vp, ctypes.c_int32, _vp, _i64, _vp, _vp]),
+    "moe_pipeline_destroy": (ctypes.c_int, [_vp]),
+    "moe_pipeline_run": (ctypes.c_int, [_vp, ctypes.c_int32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp]),
     "moe_set_option": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_int]),
     "moe_get_option": (ctypes.c_int, [ctypes.c_char_p, _vp]),
     "moe_profile_read": (ctypes.c_int, [_vp, _vp]),
@@ -399,3 +403,84 @@ def moe_layer_streamed(st: Streamer, x, Wr, bias=None, workspace: Optional[Works
                                      workspace.buf.numel(), _stream(stream), st.copy_stream.cuda_stream),
            "moe_layer_streamed")
     return y, workspace
+
+
+# ----------------------------------------------------------------------------- weight paging over several layers
+
+def pipeline_pool_pages(s: MoEShape, n_layers: int, resident_pages_per_expert: int) -> int:
+    v = _i64(0)
+    _check(_lib().moe_pipeline_pool_pages(ctypes.byref(s), int(n_layers), int(resident_pages_per_expert), ctypes.byref(v)),
+           "moe_pipeline_pool_pages")
+    return int(v.value)
+
+
+class Pipeline:
+    """A stack of MoE layers whose non-resident pages are streamed layer by layer (include/moe.h,
+    "weight paging over several layers").  ``layers``: one (host_pages pinned uint8 [pool, page_bytes],
+    host_page_table int32 [E, pages_per_expert]) pair per layer."""
+
+    def __init__(self, s: MoEShape, layers, resident_pages_per_expert: int, max_micro_batches: int, device="cuda"):
+        gu, d = pages_required(s)
+        self.shape, self.ppe, self.n_layers = s, gu + d, len(layers)
+        self.max_micro = int(max_micro_batches)
+        self.layers = list(layers)
+        for hp, ht in self.layers:
+            if not hp.is_pinned():
+                raise ValueError("host pages must be pinned host memory")
+            _host(hp, torch.uint8, (hp.shape[0], s.page_bytes), "host_pages")
+            _host(ht, torch.int32, (s.E, self.ppe), "host_page_table")
+        L = self.n_layers
+        self.pool_pages = pipeline_pool_pages(s, L, resident_pages_per_expert)
+        self.pool = torch.empty((self.pool_pages, s.page_bytes), dtype=torch.uint8, device=device)
+        self.tables = torch.empty((L, 2, s.E, self.ppe), dtype=torch.int32, device=device)
+        self.copy_stream = torch.cuda.Stream(device=device)
+        pages = (_vp * L)(*[hp.data_ptr() for hp, _ in self.layers])
+        counts = (_i64 * L)(*[int(hp.shape[0]) for hp, _ in self.layers])
+        tables = (_vp * L)(*[ht.data_ptr() for _, ht in self.layers])
+        handle = _vp(0)
+        _check(_lib().moe_pipeline_create(ctypes.byref(s), L, self.max_micro, pages, counts, tables,
+                                          int(resident_pages_per_expert), self.pool.data_ptr(), self.pool_pages,
+                                          self.tables.data_ptr(), ctypes.byref(handle)), "moe_pipeline_create")
+        self.handle = handle
+
+    def run(self, x_host, Wr, y, x_dev: Optional[torch.Tensor] = None, bias=None,
+            workspace: Optional[Workspace] = None, stream=None):
+        """x_host[l][j]: pinned host [T,H]; Wr[l]: device [E,H]; y[l][j]: device float32 [T,H]."""
+        s, L = self.shape, self.n_layers
+        n = len(x_host[0])
+        dt = s.torch_dtype
+        if x_dev is None:
+            x_dev = torch.empty((n, s.T, s.H), dtype=dt, device=self.pool.device)
+        _dev(x_dev, dt, (n, s.T, s.H), "x_dev")
+        if workspace is None:
+            workspace = Workspace(s, self.pool.device)
+        xs, ys = [], []
+        for l in range(L):
+            if len(x_host[l]) != n or len(y[l]) != n:
+                raise ValueError("every layer needs the same number of micro-batches")
+            for j in range(n):
+                if not x_host[l][j].is_pinned():
+                    raise ValueError("x_host must be pinned host memory")
+                xs.append(_host(x_host[l][j], dt, (s.T, s.H), "x_host"))
+                ys.append(_dev(y[l][j], torch.float32, (s.T, s.H), "y"))
+        wr = [_dev(Wr[l], dt, (s.E, s.H), "Wr") for l in range(L)]
+        pb = None
+        if bias is not None:
+            pb = (_vp * L)(*[_dev(b, torch.float32, (s.E,), "bias") for b in bias])
+        _check(_lib().moe_pipeline_run(self.handle, n, (_vp * (L * n))(*xs), x_dev.data_ptr(), (_vp * L)(*wr), pb,
+                                       (_vp * (L * n))(*ys), workspace.buf.data_ptr(), workspace.buf.numel(),
+                                       _stream(stream), self.copy_stream.cuda_stream), "moe_pipeline_run")
+        self._keep = (x_host, x_dev, workspace)      # the enqueued work reads these
+        return workspace
+
+    def close(self):
+        if self.handle:
+            torch.cuda.synchronize()
+            _check(_lib().moe_pipeline_destroy(self.handle), "moe_pipeline_destroy")
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

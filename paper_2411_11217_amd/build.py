@@ -40,7 +40,7 @@ def build(force: bool = True, verbose: bool = False, extra_flags=(), out: str = 
     ``extra_flags`` / ``out`` build an experimental variant next to the default library."""
     if not force and not is_stale():
         return LIB
-    build_dir = BUILD if out == LIB else BUILD + "_" + os.path.basename(out).replace(".", "_")
+    build_dir = BUILD if out == LIB else os.path.join(os.path.dirname(os.path.abspath(out)), "_build_" + os.path.basename(out).replace(".", "_"))
     os.makedirs(build_dir, exist_ok=True)
     hipcc = os.environ.get("HIPCC", "hipcc")
 

@@ -76,8 +76,8 @@ static void copy_tile(char* page_tile, char* dense, int64_t ld, int esize, bool 
     }
 }
 
-static int check_table_host(const moe_shape& s, const Geom& g, const int32_t* table, int64_t pool_pages,
-                            bool need_distinct) {
+int check_table_host(const moe_shape& s, const Geom& g, const int32_t* table, int64_t pool_pages,
+                     bool need_distinct) {
     std::vector<char> seen;
     if (need_distinct) seen.assign((size_t)pool_pages, 0);
     for (int64_t i = 0; i < (int64_t)s.E * g.ppe; ++i) {
@@ -217,6 +217,23 @@ static int layer_body(const moe_shape& s, const void* x, const void* Wr, const f
     return rc;
 }
 
+size_t layer_workspace_bytes(const moe_shape& s) {
+    moe_workspace_layout L;
+    layout(s, &L);
+    return L.total;
+}
+
+int layer_resident(const moe_shape& sh, const void* x, const void* Wr, const float* bias, const int32_t* page_table,
+                   const char* page_pool, int64_t pool_pages, float* y, char* workspace, hipStream_t st) {
+    return layer_body(sh, x, Wr, bias, y, workspace, st,
+                      [&](const void* xp, const int32_t* offsets, const float* row_w, void* h, float* out,
+                          int32_t* status, hipEvent_t mid) {
+                          FfnArgs a{xp, offsets, page_table, page_pool, pool_pages, row_w, h, out,
+                                    status, 0, sh.E, 0, mid};
+                          return launch_expert_ffn(sh, a, st);
+                      });
+}
+
 }  // namespace moe
 
 using namespace moe;
@@ -335,19 +352,10 @@ int moe_layer(const moe_shape* s, const void* x, const void* Wr, const float* bi
     if (s->T == 0) return MOE_OK;
     if (!x || !Wr || !page_table || !page_pool || !y || !workspace || pool_pages <= 0)
         return MOE_ERR_INVALID_ARG;
-    moe_workspace_layout L;
-    layout(*s, &L);
-    if (workspace_bytes < L.total) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    if (workspace_bytes < layer_workspace_bytes(*s)) return MOE_ERR_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_INVALID_ARG;
-    hipStream_t st = (hipStream_t)stream;
-    const moe_shape sh = *s;
-    return layer_body(sh, x, Wr, bias, y, (char*)workspace, st,
-                      [&](const void* xp, const int32_t* offsets, const float* row_w, void* h, float* out,
-                          int32_t* status, hipEvent_t mid) {
-                          FfnArgs a{xp, offsets, page_table, (const char*)page_pool, pool_pages, row_w, h, out,
-                                    status, 0, sh.E, 0, mid};
-                          return launch_expert_ffn(sh, a, st);
-                      });
+    return layer_resident(*s, x, Wr, bias, page_table, (const char*)page_pool, pool_pages, y, (char*)workspace,
+                          (hipStream_t)stream);
 }
 
 int moe_set_option(const char* name, int value) {

@@ -31,6 +31,15 @@ struct Geom {
 int validate_shape(const moe_shape* s);          // MOE_OK or error
 Geom geometry(const moe_shape& s);               // shape must be valid
 
+// MOE_OK, MOE_ERR_PAGE_NOT_RESIDENT (an entry outside [0, pool_pages)) or, with need_distinct,
+// MOE_ERR_INVALID_ARG when two entries name the same slot.  table: host int32[E][ppe].
+int check_table_host(const moe_shape& s, const Geom& g, const int32_t* table, int64_t pool_pages, bool need_distinct);
+
+// The layer with all pages resident, enqueued on st (arguments already validated).
+size_t layer_workspace_bytes(const moe_shape& s);
+int layer_resident(const moe_shape& s, const void* x, const void* Wr, const float* bias, const int32_t* page_table,
+                   const char* page_pool, int64_t pool_pages, float* y, char* workspace, hipStream_t st);
+
 // thread-local record of the last failing HIP call
 void set_hip_error(hipError_t e);
 #define MOE_HIP_TRY(expr)                               \

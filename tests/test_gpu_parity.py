@@ -237,3 +237,38 @@ def test_streamed_pages_match_resident_pages_bitwise():
         st.close()
     ref = res.oracle_layer()
     assert_close(y_res.cpu().numpy(), ref["y"], "bf16", "streamed case vs oracle")
+
+
+@pytest.mark.parametrize("resident", ["none", "some", "all"])
+def test_multi_layer_weight_paging_matches_resident_layers_bitwise(resident):
+    """Three layers, four micro-batches, two passes (the second starts with the first layer already
+    prefetched): every output equals moe_layer on that layer's resident pages, bit for bit."""
+    base = scaled(MED["bf16_top2_of_4"], T=96)
+    s = shape_of(base)
+    gu, d = M.pages_required(s)
+    ppe = gu + d
+    n_res = {"none": 0, "some": gu // 2 + 1, "all": ppe}[resident]
+    L, n = 3, 4
+    cases = [Case(scaled(base, seed=base.seed + 10 * l)) for l in range(L)]
+    hosts = [M.PagedWeights(s, c.inp["W1"], c.inp["W3"], c.inp["W2"], order=torch.Generator().manual_seed(40 + l),
+                            extra_pages=2, pin=True) for l, c in enumerate(cases)]
+    g = torch.Generator().manual_seed(77)
+    x_host = [[torch.randn((s.T, s.H), generator=g).to(torch.bfloat16).pin_memory() for _ in range(n)] for _ in range(L)]
+    want = [[M.moe_layer(s, x_host[l][j].cuda(), cases[l].Wr, cases[l].pw.table_dev, cases[l].pw.pages_dev)[0]
+             for j in range(n)] for l in range(L)]
+    torch.cuda.synchronize()
+    pipe = M.Pipeline(s, [(h.pages_host, h.table_host) for h in hosts], n_res, max_micro_batches=n)
+    try:
+        for rep in range(2):
+            y = [[torch.zeros((s.T, s.H), dtype=torch.float32, device="cuda") for _ in range(n)] for _ in range(L)]
+            ws = pipe.run(x_host, [c.Wr for c in cases], y)
+            torch.cuda.synchronize()
+            assert ws.view("status").cpu().tolist() == [0, 0, 0, 0]
+            for l in range(L):
+                for j in range(n):
+                    assert torch.equal(y[l][j], want[l][j]), (resident, rep, l, j)
+    finally:
+        pipe.close()
+    ref = cases[0].oracle_layer()
+    y0, _ = M.moe_layer(s, cases[0].x, cases[0].Wr, cases[0].pw.table_dev, cases[0].pw.pages_dev)
+    assert_close(y0.cpu().numpy(), ref["y"], "bf16", "paging case, layer 0 vs oracle")

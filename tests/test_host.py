@@ -172,3 +172,23 @@ def test_null_and_small_workspace_errors_without_gpu():
     assert lib.moe_route(ctypes.byref(s0), None, None, None, None, None, None, None) == 0   # T == 0: nothing to do
     assert lib.moe_set_option(b"no_such_option", 1) == B.ERR_INVALID_ARG
     assert M.get_option("xcd_remap") in (0, 1)
+
+
+def test_pipeline_pool_size_and_argument_errors_without_gpu():
+    # pool = every layer's resident pages + a double buffer for one layer's streamed pages
+    s = M.make_shape(8, 256, 384, 3, 1, "bf16", 3 * 16384)
+    gu, d = M.pages_required(s)
+    ppe = gu + d
+    assert M.pipeline_pool_pages(s, 4, 0) == 2 * 3 * ppe
+    assert M.pipeline_pool_pages(s, 4, ppe) == 4 * 3 * ppe
+    assert M.pipeline_pool_pages(s, 4, 5) == 4 * 3 * 5 + 2 * 3 * (ppe - 5)
+    lib = B._lib()
+    out = ctypes.c_int64(0)
+    assert lib.moe_pipeline_pool_pages(ctypes.byref(s), 0, 0, ctypes.byref(out)) == B.ERR_INVALID_ARG
+    assert lib.moe_pipeline_pool_pages(ctypes.byref(s), 1, ppe + 1, ctypes.byref(out)) == B.ERR_INVALID_ARG
+    assert lib.moe_pipeline_pool_pages(ctypes.byref(s), 1, 0, None) == B.ERR_INVALID_ARG
+    handle = ctypes.c_void_p(0)
+    assert lib.moe_pipeline_create(ctypes.byref(s), 2, 4, None, None, None, 0, None, 0, None, ctypes.byref(handle)) \
+        == B.ERR_INVALID_ARG
+    assert lib.moe_pipeline_run(None, 1, None, None, None, None, None, None, 0, None, None) == B.ERR_INVALID_ARG
+    assert lib.moe_pipeline_destroy(None) == B.ERR_INVALID_ARG
