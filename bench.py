@@ -40,6 +40,13 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="instead of the layer, run a plain device copy of 1 GiB ten times (calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc against known traffic)")
+    ap.add_argument("--pipeline", action="store_true",
+                    help="instead of the headline step, time the multi-layer weight-paging pipeline (moe_pipeline_run) "
+                         "on --config's layer shape: --layers layers (sharing one set of host pages), --micro-batches "
+                         "micro-batches of T / micro-batches tokens, --resident-fraction of every expert's pages kept in HBM")
+    ap.add_argument("--layers", type=int, default=2)
+    ap.add_argument("--micro-batches", type=int, default=4)
+    ap.add_argument("--resident-fraction", type=float, default=0.5)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -68,6 +75,8 @@ def main():
     for o in args.option:
         name, val = o.split("=")
         M.set_option(name, int(val))
+    if args.pipeline:
+        return pipeline_bench(args, cfg, M, make_inputs)
     s = M.make_shape(cfg.T, cfg.H, cfg.F, cfg.E, cfg.k, cfg.dtype, cfg.page_bytes)
     t0 = time.time()
     inp = make_inputs(cfg, threads=16)
@@ -171,6 +180,61 @@ def main():
     print(json.dumps(out), flush=True)
     if streamer is not None:
         streamer.close()
+
+
+def pipeline_bench(args, cfg, M, make_inputs):
+    """Times passes of moe_pipeline_run: per layer, n micro-batches are computed while the non-resident pages of
+    the next layer cross the host link.  Reported next to the paper's per-layer latency model
+    T = max(comm_cpu_to_gpu, T_gpu) (its section 4.2; no CPU work here), with T_gpu measured by the same
+    pipeline holding every page resident."""
+    import torch
+    n, L = args.micro_batches, args.layers
+    mu = cfg.T // n
+    s = M.make_shape(mu, cfg.H, cfg.F, cfg.E, cfg.k, cfg.dtype, cfg.page_bytes)
+    inp = make_inputs(cfg, threads=16)
+    host = M.PagedWeights(s, inp["W1"], inp["W3"], inp["W2"], pin=True)
+    del inp["W1"], inp["W3"], inp["W2"]
+    ppe = host.ppe
+    x_host = [[inp["x"][j * mu:(j + 1) * mu].contiguous().pin_memory() for j in range(n)] for _ in range(L)]
+    Wr = [inp["Wr"].cuda()] * L
+    bias = None if inp["bias"] is None else [inp["bias"].cuda()] * L
+    y = [[torch.empty((mu, cfg.H), dtype=torch.float32, device="cuda")] * n for _ in range(L)]   # results overwrite each other
+    layers = [(host.pages_host, host.table_host)] * L
+
+    def timed(n_res):
+        pipe = M.Pipeline(s, layers, n_res, max_micro_batches=n)
+        ws = None
+        for _ in range(max(args.warmup // 5, 1)):
+            ws = pipe.run(x_host, Wr, y, bias=bias, workspace=ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = max(args.steps // 10, 2)
+        for _ in range(reps):
+            pipe.run(x_host, Wr, y, bias=bias, workspace=ws)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / (reps * L)
+        pipe.close()
+        del pipe
+        torch.cuda.empty_cache()
+        return ms
+
+    n_res = int(round(args.resident_fraction * ppe))
+    gpu_ms = timed(ppe)
+    ms = timed(n_res)
+    link_bytes = cfg.E * (ppe - n_res) * cfg.page_bytes
+    out = {
+        "metric": "MoE layer pipeline tokens/s per layer (weights paged from pinned host memory)",
+        "value": round(cfg.T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "higher_is_better": True,
+        "ms_per_layer": round(ms, 3), "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name + " (layer shape)", "layers": L, "micro_batches": n, "micro_tokens": mu,
+                   "resident_pages_per_expert": n_res, "pages_per_expert": ppe, "resident_fraction": round(n_res / ppe, 4)},
+        "host_link": {"bytes_per_layer": link_bytes, "gbs": round(link_bytes / (ms * 1e-3) / 1e9, 2)},
+        "model": {"gpu_ms_per_layer_all_resident": round(gpu_ms, 3),
+                  "note": "per-layer latency = max(link bytes / link rate, gpu_ms); link rate ~55.7 GB/s measured on the "
+                          "fully streamed workload"},
+    }
+    out["model"]["predicted_ms"] = round(max(link_bytes / 55.7e9 * 1e3, gpu_ms), 3)
+    print(json.dumps(out), flush=True)
 
 
 if __name__ == "__main__":
