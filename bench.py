@@ -44,6 +44,10 @@ def main():
                     help="instead of the headline step, time the multi-layer weight-paging pipeline (moe_pipeline_run) "
                          "on --config's layer shape: --layers layers (sharing one set of host pages), --micro-batches "
                          "micro-batches of T / micro-batches tokens, --resident-fraction of every expert's pages kept in HBM")
+    ap.add_argument("--tasks", action="store_true",
+                    help="instead of the headline step, time the post-attention task (O projection, residual + norm, MoE "
+                         "layer) and the pre-attention task (residual + norm, QKV projection) on --config's layer shape, "
+                         "with attention width H and a QKV width of 1.5 H (32 query and 8 key/value heads of 128)")
     ap.add_argument("--layers", type=int, default=2)
     ap.add_argument("--micro-batches", type=int, default=4)
     ap.add_argument("--resident-fraction", type=float, default=0.5)
@@ -77,6 +81,8 @@ def main():
         M.set_option(name, int(val))
     if args.pipeline:
         return pipeline_bench(args, cfg, M, make_inputs)
+    if args.tasks:
+        return tasks_bench(args, cfg, M, make_inputs)
     s = M.make_shape(cfg.T, cfg.H, cfg.F, cfg.E, cfg.k, cfg.dtype, cfg.page_bytes)
     t0 = time.time()
     inp = make_inputs(cfg, threads=16)
@@ -180,6 +186,59 @@ def main():
     print(json.dumps(out), flush=True)
     if streamer is not None:
         streamer.close()
+
+
+def tasks_bench(args, cfg, M, make_inputs):
+    """Times the two GPU tasks of the paper's pipeline (its section 4.1) and their stages on one micro-batch."""
+    import torch
+    s = M.make_shape(cfg.T, cfg.H, cfg.F, cfg.E, cfg.k, cfg.dtype, cfg.page_bytes)
+    inp = make_inputs(cfg, threads=16)
+    pw = M.PagedWeights(s, inp["W1"], inp["W3"], inp["W2"])
+    T, H, Nq = cfg.T, cfg.H, cfg.H * 3 // 2
+    o_shape, q_shape = M.make_linear_shape(T, H, H, cfg.page_bytes), M.make_linear_shape(T, H, Nq, cfg.page_bytes)
+    n_exp, n_o, n_q = pw.pool_pages, M.linear_pages_required(o_shape), M.linear_pages_required(q_shape)
+    g = torch.Generator().manual_seed(1)
+    pool = torch.empty((n_exp + n_o + n_q, cfg.page_bytes), dtype=torch.uint8)
+    pool[:n_exp] = pw.pages_host
+    o_table = torch.arange(n_exp, n_exp + n_o, dtype=torch.int32)
+    q_table = torch.arange(n_exp + n_o, n_exp + n_o + n_q, dtype=torch.int32)
+    M.linear_pack(o_shape, (torch.randn((H, H), generator=g) * 0.02).to(torch.bfloat16), o_table, pool)
+    M.linear_pack(q_shape, (torch.randn((Nq, H), generator=g) * 0.02).to(torch.bfloat16), q_table, pool)
+    pool, o_table, q_table, table = pool.cuda(), o_table.cuda(), q_table.cuda(), pw.table_host.cuda()
+    attn = torch.randn((T, H), generator=g).to(torch.bfloat16).cuda()
+    hidden = torch.randn((T, H), generator=g).cuda()
+    gamma = torch.ones(H).cuda()
+    Wr = inp["Wr"].cuda()
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    hm, x_moe, y, _ws = M.moe_post_attention(s, o_shape, attn, hidden, o_table, gamma, 1e-5, Wr, table, pool)
+    o = M.moe_linear(o_shape, attn, o_table, pool)
+    ms = {
+        "post_attention_task": timed(lambda: M.moe_post_attention(s, o_shape, attn, hidden, o_table, gamma, 1e-5, Wr, table, pool)),
+        "pre_attention_task": timed(lambda: M.moe_pre_attention(q_shape, hm, y, gamma, 1e-5, q_table, pool)),
+        "o_projection": timed(lambda: M.moe_linear(o_shape, attn, o_table, pool)),
+        "qkv_projection": timed(lambda: M.moe_linear(q_shape, x_moe, q_table, pool)),
+        "add_rmsnorm": timed(lambda: M.moe_add_rmsnorm(hidden, o, gamma, 1e-5)),
+        "cast_bf16_qkv": timed(lambda: M.moe_cast_bf16(torch.empty((T, Nq), dtype=torch.float32, device="cuda"))),
+    }
+    out = {"metric": "GPU tasks around the MoE layer, ms per micro-batch (includes the binding's output allocations)",
+           "config": {"workload": cfg.name + " (layer shape)", "T": T, "H": H, "qkv_width": Nq},
+           "ms": {k: round(v, 4) for k, v in ms.items()},
+           "tflops": {"o_projection": round(2.0 * T * H * H / ms["o_projection"] / 1e9, 1),
+                      "qkv_projection": round(2.0 * T * H * Nq / ms["qkv_projection"] / 1e9, 1)},
+           "add_rmsnorm_gbs": round((2 * T * H * 4 + T * H * 4 + T * H * 2) / ms["add_rmsnorm"] / 1e6, 1)}
+    print(json.dumps(out), flush=True)
 
 
 def pipeline_bench(args, cfg, M, make_inputs):

@@ -247,6 +247,68 @@ int moe_pipeline_run(moe_pipeline* p, int32_t n_micro, const void* const* x_host
                      const void* const* Wr, const float* const* bias, float* const* y,
                      void* workspace, size_t workspace_bytes, void* stream, void* copy_stream);
 
+/* ------------------------------------------------------------------ the dense neighbours of the layer
+ *
+ * The paper's GPU tasks around the MoE FFN (section 4.1): the post-attention task is
+ * "primarily O projection and MoE FFN", the pre-attention task "mainly layer norm and
+ * QKV projection" of the next micro-batch.  The paper does not write their arithmetic
+ * down; the forms are those of the models it evaluates: bias-free linear maps, RMS
+ * normalisation with a learned scale, an f32 residual stream.  bf16 only.
+ *
+ * A dense weight W[N][K] is paged like an expert's W2: tiles of 128 output features x
+ * 64 reduction elements ordered [n/128][k/64], the last page zero padded; page_table is
+ * int32[pages] (moe_linear_pages_required).  K a multiple of 64 (>= 128), N of 128.
+ */
+typedef struct moe_linear_shape {
+    int32_t T;          /* rows (tokens) */
+    int32_t K;          /* input features */
+    int32_t N;          /* output features */
+    int32_t dtype;      /* MOE_DTYPE_BF16 */
+    int64_t page_bytes;
+} moe_linear_shape;
+
+#define MOE_LINEAR_WORKSPACE_BYTES 16
+
+int moe_linear_pages_required(const moe_linear_shape* s, int64_t* pages);
+/* Host packer.  W: host bf16[N][K]; page_table: host int32[pages], distinct slots in
+ * [0, pool_pages); pages_out: host, pool_pages * page_bytes. */
+int moe_linear_pack(const moe_linear_shape* s, const void* W, const int32_t* page_table, int64_t pool_pages,
+                    void* pages_out);
+/* out[t][n] = sum_k x[t][k] W[n][k].  x: device bf16[T][K]; page_table: device
+ * int32[pages]; out: device float[T][N]; workspace: device, MOE_LINEAR_WORKSPACE_BYTES;
+ * status: device int32[4] or NULL (bit 0 of [0]: a page-table entry outside the pool). */
+int moe_linear(const moe_linear_shape* s, const void* x, const int32_t* page_table, const void* page_pool,
+               int64_t pool_pages, float* out, void* workspace, size_t workspace_bytes, int32_t* status, void* stream);
+/* s = hidden + delta (hidden may be NULL: s = delta), written to hidden_out when not
+ * NULL; x_out = bf16(s / sqrt(mean(s^2) + eps) * gamma).  hidden, delta, hidden_out:
+ * device float[T][H]; gamma: device float[H]; x_out: device bf16[T][H].  H a multiple
+ * of 4, at most 8192. */
+int moe_add_rmsnorm(int32_t T, int32_t H, const float* hidden, const float* delta, const float* gamma, float eps,
+                    float* hidden_out, void* x_out, void* stream);
+/* out = bf16(in), round to nearest even; n a multiple of 4. */
+int moe_cast_bf16(int64_t n, const float* in, void* out, void* stream);
+
+/* Post-attention task: o = attn Wo^T; hidden_mid = hidden + o; x_moe = norm(hidden_mid);
+ * y = MoE layer(x_moe).  (The caller adds y to hidden_mid, or passes both to
+ * moe_pre_attention, which does.)  attn: device bf16[T][o_proj->K]; hidden: device
+ * float[T][H]; o_table: device page table of Wo, slots in the SAME pool as the experts';
+ * hidden_mid: device float[T][H]; x_moe: device bf16[T][H]; y: device float[T][H];
+ * workspace: device, 256-byte aligned, moe_post_attention_workspace_bytes; the MoE
+ * layer's intermediates are at its start (moe_workspace_layout_get). */
+int moe_post_attention_workspace_bytes(const moe_shape* s, size_t* bytes);
+int moe_post_attention(const moe_shape* s, const moe_linear_shape* o_proj, const void* attn, const float* hidden,
+                       const int32_t* o_table, const float* norm_gamma, float eps, const void* Wr, const float* bias,
+                       const int32_t* page_table, const void* page_pool, int64_t pool_pages,
+                       float* hidden_mid, void* x_moe, float* y, void* workspace, size_t workspace_bytes, void* stream);
+/* Pre-attention task: hidden_out = hidden + delta; x_norm = norm(hidden_out);
+ * qkv = x_norm Wqkv^T (f32), and its bf16 copy when qkv_bf16 != NULL (what goes to the
+ * host for the attention).  hidden may be NULL.  workspace: device,
+ * MOE_LINEAR_WORKSPACE_BYTES. */
+int moe_pre_attention(const moe_linear_shape* qkv_proj, const float* hidden, const float* delta, const float* norm_gamma,
+                      float eps, const int32_t* qkv_table, const void* page_pool, int64_t pool_pages,
+                      float* hidden_out, void* x_norm, float* qkv, void* qkv_bf16, void* workspace, size_t workspace_bytes,
+                      void* stream);
+
 /* ------------------------------------------------------------------ tuning knobs
  * Named integer options for experiments (kernel variants, tile order); unknown
  * names give MOE_ERR_INVALID_ARG.  Defaults are the measured best. */

@@ -78,6 +78,14 @@ _SIGNATURES = {
     "moe_pipeline_create": (ctypes.c_int, [_vp, ctypes.c_int32, ctypes.c_int32, _vp, _vp, _vp, ctypes.c_int32, _vp, _i64, _vp, _vp]),
     "moe_pipeline_destroy": (ctypes.c_int, [_vp]),
     "moe_pipeline_run": (ctypes.c_int, [_vp, ctypes.c_int32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp]),
+    "moe_linear_pages_required": (ctypes.c_int, [_vp, _vp]),
+    "moe_linear_pack": (ctypes.c_int, [_vp, _vp, _vp, _i64, _vp]),
+    "moe_linear": (ctypes.c_int, [_vp] * 4 + [_i64, _vp, _vp, _sz, _vp, _vp]),
+    "moe_add_rmsnorm": (ctypes.c_int, [ctypes.c_int32, ctypes.c_int32, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp]),
+    "moe_cast_bf16": (ctypes.c_int, [_i64, _vp, _vp, _vp]),
+    "moe_post_attention_workspace_bytes": (ctypes.c_int, [_vp, _vp]),
+    "moe_post_attention": (ctypes.c_int, [_vp] * 6 + [ctypes.c_float] + [_vp] * 4 + [_i64] + [_vp] * 4 + [_sz, _vp]),
+    "moe_pre_attention": (ctypes.c_int, [_vp] * 4 + [ctypes.c_float, _vp, _vp, _i64] + [_vp] * 5 + [_sz, _vp]),
     "moe_set_option": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_int]),
     "moe_get_option": (ctypes.c_int, [ctypes.c_char_p, _vp]),
     "moe_profile_read": (ctypes.c_int, [_vp, _vp]),
@@ -484,3 +492,114 @@ class Pipeline:
             self.close()
         except Exception:
             pass
+
+
+# ----------------------------------------------------------------------------- dense neighbours of the layer
+
+class LinearShape(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int32), ("K", ctypes.c_int32), ("N", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("page_bytes", ctypes.c_int64)]
+
+
+def make_linear_shape(T, K, N, page_bytes) -> LinearShape:
+    return LinearShape(int(T), int(K), int(N), DTYPE_BF16, int(page_bytes))
+
+
+def linear_pages_required(ls: LinearShape) -> int:
+    v = _i64(0)
+    _check(_lib().moe_linear_pages_required(ctypes.byref(ls), ctypes.byref(v)), "moe_linear_pages_required")
+    return int(v.value)
+
+
+def linear_pack(ls: LinearShape, W: torch.Tensor, page_table: torch.Tensor, pages_out: torch.Tensor):
+    """Writes the pages of W (host bf16 [N,K]) into pages_out (host uint8 [pool_pages, page_bytes]) at the slots
+    page_table (host int32 [pages]) names."""
+    n = linear_pages_required(ls)
+    pw = _host(W, torch.bfloat16, (ls.N, ls.K), "W")
+    pt = _host(page_table, torch.int32, (n,), "page_table")
+    pp = _host(pages_out, torch.uint8, (pages_out.shape[0], ls.page_bytes), "pages_out")
+    _check(_lib().moe_linear_pack(ctypes.byref(ls), pw, pt, int(pages_out.shape[0]), pp), "moe_linear_pack")
+
+
+def moe_linear(ls: LinearShape, x, page_table, page_pool, status=None, stream=None) -> torch.Tensor:
+    px = _dev(x, torch.bfloat16, (ls.T, ls.K), "x")
+    pt = _dev(page_table, torch.int32, (linear_pages_required(ls),), "page_table")
+    pp = _dev(page_pool, torch.uint8, None, "page_pool")
+    ps = _dev(status, torch.int32, (4,), "status")
+    out = torch.empty((ls.T, ls.N), dtype=torch.float32, device=x.device)
+    ws = torch.empty(16, dtype=torch.uint8, device=x.device)
+    _check(_lib().moe_linear(ctypes.byref(ls), px, pt, pp, int(page_pool.shape[0]), out.data_ptr(), ws.data_ptr(), 16, ps,
+                             _stream(stream)), "moe_linear")
+    return out
+
+
+def moe_add_rmsnorm(hidden, delta, gamma, eps: float, want_hidden: bool = True, stream=None):
+    """-> (hidden + delta as float32 or None, bf16 normalised rows)"""
+    T, H = delta.shape
+    ph = _dev(hidden, torch.float32, (T, H), "hidden")
+    pd = _dev(delta, torch.float32, (T, H), "delta")
+    pg = _dev(gamma, torch.float32, (H,), "gamma")
+    hs = torch.empty((T, H), dtype=torch.float32, device=delta.device) if want_hidden else None
+    x = torch.empty((T, H), dtype=torch.bfloat16, device=delta.device)
+    _check(_lib().moe_add_rmsnorm(T, H, ph, pd, pg, float(eps), None if hs is None else hs.data_ptr(), x.data_ptr(),
+                                  _stream(stream)), "moe_add_rmsnorm")
+    return hs, x
+
+
+def moe_cast_bf16(t: torch.Tensor, stream=None) -> torch.Tensor:
+    _dev(t, torch.float32, None, "in")
+    out = torch.empty(t.shape, dtype=torch.bfloat16, device=t.device)
+    _check(_lib().moe_cast_bf16(t.numel(), t.data_ptr(), out.data_ptr(), _stream(stream)), "moe_cast_bf16")
+    return out
+
+
+def post_attention_workspace_bytes(s: MoEShape) -> int:
+    v = _sz(0)
+    _check(_lib().moe_post_attention_workspace_bytes(ctypes.byref(s), ctypes.byref(v)), "moe_post_attention_workspace_bytes")
+    return int(v.value)
+
+
+def moe_post_attention(s: MoEShape, o_proj: LinearShape, attn, hidden, o_table, norm_gamma, eps, Wr, page_table, page_pool,
+                       bias=None, stream=None):
+    """-> (hidden_mid f32, x_moe bf16, y f32, workspace bytes tensor)"""
+    gu, d = pages_required(s)
+    pa = _dev(attn, torch.bfloat16, (s.T, o_proj.K), "attn")
+    ph = _dev(hidden, torch.float32, (s.T, s.H), "hidden")
+    po = _dev(o_table, torch.int32, (linear_pages_required(o_proj),), "o_table")
+    pg = _dev(norm_gamma, torch.float32, (s.H,), "norm_gamma")
+    pw = _dev(Wr, torch.bfloat16, (s.E, s.H), "Wr")
+    pb = _dev(bias, torch.float32, (s.E,), "bias")
+    pt = _dev(page_table, torch.int32, (s.E, gu + d), "page_table")
+    pp = _dev(page_pool, torch.uint8, None, "page_pool")
+    dev = attn.device
+    hidden_mid = torch.empty((s.T, s.H), dtype=torch.float32, device=dev)
+    x_moe = torch.empty((s.T, s.H), dtype=torch.bfloat16, device=dev)
+    y = torch.empty((s.T, s.H), dtype=torch.float32, device=dev)
+    nbytes = post_attention_workspace_bytes(s)
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+    off = (-ws.data_ptr()) % 256
+    _check(_lib().moe_post_attention(ctypes.byref(s), ctypes.byref(o_proj), pa, ph, po, pg, float(eps), pw, pb, pt, pp,
+                                     int(page_pool.shape[0]), hidden_mid.data_ptr(), x_moe.data_ptr(), y.data_ptr(),
+                                     ws.data_ptr() + off, nbytes, _stream(stream)), "moe_post_attention")
+    return hidden_mid, x_moe, y, ws
+
+
+def moe_pre_attention(qkv_proj: LinearShape, hidden, delta, norm_gamma, eps, qkv_table, page_pool, want_bf16=True, stream=None):
+    """-> (hidden_out f32, x_norm bf16, qkv f32, qkv bf16 or None)"""
+    T, H = delta.shape
+    ph = _dev(hidden, torch.float32, (T, H), "hidden")
+    pd = _dev(delta, torch.float32, (qkv_proj.T, qkv_proj.K), "delta")
+    pg = _dev(norm_gamma, torch.float32, (H,), "norm_gamma")
+    pt = _dev(qkv_table, torch.int32, (linear_pages_required(qkv_proj),), "qkv_table")
+    pp = _dev(page_pool, torch.uint8, None, "page_pool")
+    dev = delta.device
+    hidden_out = torch.empty((T, H), dtype=torch.float32, device=dev)
+    x_norm = torch.empty((T, H), dtype=torch.bfloat16, device=dev)
+    qkv = torch.empty((T, qkv_proj.N), dtype=torch.float32, device=dev)
+    qkv16 = torch.empty((T, qkv_proj.N), dtype=torch.bfloat16, device=dev) if want_bf16 else None
+    ws = torch.empty(16, dtype=torch.uint8, device=dev)
+    _check(_lib().moe_pre_attention(ctypes.byref(qkv_proj), ph, pd, pg, float(eps), pt, pp, int(page_pool.shape[0]),
+                                    hidden_out.data_ptr(), x_norm.data_ptr(), qkv.data_ptr(),
+                                    None if qkv16 is None else qkv16.data_ptr(), ws.data_ptr(), 16, _stream(stream)),
+           "moe_pre_attention")
+    return hidden_out, x_norm, qkv, qkv16

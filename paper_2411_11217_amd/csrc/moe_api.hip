@@ -64,7 +64,7 @@ static inline int64_t tile_chunk_offset(int esize, int n, int c) {
 
 // Copies one 128 x 64 tile between a dense row-major matrix (leading dimension
 // ld elements) and its page image.  to_page: dense -> page, else page -> dense.
-static void copy_tile(char* page_tile, char* dense, int64_t ld, int esize, bool to_page) {
+void copy_tile(char* page_tile, char* dense, int64_t ld, int esize, bool to_page) {
     const int chunks = kTileK * esize / 16;
     for (int n = 0; n < kTileN; ++n) {
         char* drow = dense + (int64_t)n * ld * esize;

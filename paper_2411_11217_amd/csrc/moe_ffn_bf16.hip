@@ -43,6 +43,7 @@
 // Measured against 8 wavefronts of 128 x 64 each: a 128 x 128 wavefront tile needs
 // 8 LDS fetches per 16 MFMAs instead of 12, a third less LDS traffic; the chip is
 // power limited under this load, the clock rises and the loop runs ~10 % faster.
+#include <algorithm>
 #include <mutex>
 #include <type_traits>
 
@@ -401,5 +402,42 @@ int launch_expert_ffn_bf16(const moe_shape& s, const Geom& g, const FfnArgs& a, 
     }
     return launch_stages<1, 2>(p, gemm_grid(p.NT, R, BM, n_exp), st);
 }
+
+// y = x W^T for a dense weight matrix held as pages: the down-projection kernel with one "expert"
+// that owns all T rows (offsets = {0, T}) and no row weight.
+int launch_linear_bf16(const LinearArgs& a, hipStream_t st) {
+    GemmParams p{};
+    p.A = (const char*)a.x;
+    p.lda_bytes = (int64_t)a.K * 2;
+    p.offsets = a.offsets;
+    p.table = a.page_table;
+    p.pool = a.pool;
+    p.page_bytes = a.page_bytes;
+    p.tile_bytes = (int64_t)kTileN * kTileK * 2;
+    p.pool_pages = (int32_t)std::min<int64_t>(a.pool_pages, 0x7fffffff);
+    p.tpp = (int32_t)(a.page_bytes / p.tile_bytes);
+    p.ppe = (int32_t)a.pages;
+    p.group_base = 0;
+    p.KT = a.K / kTileK;
+    p.n_page_tiles = a.N / kTileN;
+    p.e_begin = 0;
+    p.e_end = 1;
+    p.table_row_mod = 0;
+    p.out = a.out;
+    p.ldo = a.N;
+    p.n_cols = a.N;
+    p.row_w = nullptr;
+    p.status = a.status;
+    p.xcd_remap = get_opt(OPT_XCD_REMAP);
+    p.tile_order = get_opt(OPT_TILE_ORDER);
+    const int wide_tiles = (p.n_page_tiles + 1) / 2;
+    if ((int64_t)(a.T / BM + 1) * wide_tiles < 2 * kComputeUnits) {       // too few 256-wide tiles to fill the chip
+        p.NT = p.n_page_tiles;
+        return launch_stages<1, 1>(p, gemm_grid(p.NT, a.T, BM, 1), st);
+    }
+    p.NT = wide_tiles;
+    return launch_stages<1, 2>(p, gemm_grid(p.NT, a.T, BM, 1), st);
+}
+
 
 }  // namespace moe

@@ -81,6 +81,23 @@ int launch_expert_ffn(const moe_shape& s, const FfnArgs& a, hipStream_t st);
 int launch_expert_ffn_bf16(const moe_shape& s, const Geom& g, const FfnArgs& a, hipStream_t st);
 int launch_expert_ffn_f32(const moe_shape& s, const Geom& g, const FfnArgs& a, hipStream_t st);
 
+// Dense y = x W^T over paged weights (bf16 in, f32 out); offsets: device int32[2] = {0, T}.
+struct LinearArgs {
+    const void* x;             // bf16 [T][K]
+    int T, K, N;
+    const int32_t* offsets;
+    const int32_t* page_table; // device [pages]
+    const char* pool;
+    int64_t pool_pages, page_bytes, pages;
+    float* out;                // [T][N]
+    int32_t* status;           // [4] or null
+};
+int launch_linear_bf16(const LinearArgs& a, hipStream_t st);
+
+// Copies one 128 x 64 weight tile between a dense row-major matrix (leading dimension ld elements)
+// and its page image.
+void copy_tile(char* page_tile, char* dense, int64_t ld, int esize, bool to_page);
+
 int launch_combine(const moe_shape& s, const float* out, const int32_t* row_of, const float* topk_w,
                    float* y, hipStream_t st);
 
