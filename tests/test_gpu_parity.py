@@ -272,3 +272,27 @@ def test_multi_layer_weight_paging_matches_resident_layers_bitwise(resident):
     ref = cases[0].oracle_layer()
     y0, _ = M.moe_layer(s, cases[0].x, cases[0].Wr, cases[0].pw.table_dev, cases[0].pw.pages_dev)
     assert_close(y0.cpu().numpy(), ref["y"], "bf16", "paging case, layer 0 vs oracle")
+
+
+def test_layer_can_be_captured_in_a_hip_graph_and_replayed():
+    """The layer call only launches kernels (status words are cleared by a kernel, not a memset), so it can be
+    captured; every replay, with eager work in between, equals the eager result."""
+    case = Case(MED["bf16_top2_of_4"])
+    s = case.shape
+    ws = M.Workspace(s)
+    y = torch.empty((s.T, s.H), dtype=torch.float32, device="cuda")
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        M.moe_layer(s, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev, workspace=ws, y=y, stream=st)
+        st.synchronize()
+        want = y.clone()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            M.moe_layer(s, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev, workspace=ws, y=y, stream=st)
+        for rep in range(4):
+            y.zero_()
+            ws.buf.zero_()
+            (case.x.float() @ case.x.float().T).sum().item()       # eager work and a synchronisation between replays
+            g.replay()
+            st.synchronize()
+            assert torch.equal(y, want), rep
