@@ -257,7 +257,7 @@ int moe_pipeline_run(moe_pipeline* p, int32_t n_micro, const void* const* x_host
  *
  * A dense weight W[N][K] is paged like an expert's W2: tiles of 128 output features x
  * 64 reduction elements ordered [n/128][k/64], the last page zero padded; page_table is
- * int32[pages] (moe_linear_pages_required).  K a multiple of 64 (>= 128), N of 128.
+ * int32[pages] (moe_linear_pages_required).  K and N multiples of 128.
  */
 typedef struct moe_linear_shape {
     int32_t T;          /* rows (tokens) */

@@ -20,7 +20,7 @@ namespace {
 int validate_linear(const moe_linear_shape* s) {
     if (!s) return MOE_ERR_INVALID_ARG;
     if (s->dtype != MOE_DTYPE_BF16) return MOE_ERR_UNSUPPORTED_DTYPE;
-    if (s->T < 0 || s->K < 128 || s->N < 128 || s->K % kTileK != 0 || s->N % kTileN != 0) return MOE_ERR_INVALID_ARG;
+    if (s->T < 0 || s->K < 128 || s->N < 128 || s->K % 128 != 0 || s->N % kTileN != 0) return MOE_ERR_INVALID_ARG;
     if ((int64_t)s->T > 0x3fffffff) return MOE_ERR_INVALID_ARG;
     const int64_t tile = (int64_t)kTileN * kTileK * 2;
     if (s->page_bytes <= 0 || s->page_bytes % tile != 0) return MOE_ERR_INVALID_ARG;

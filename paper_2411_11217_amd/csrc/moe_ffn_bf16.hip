@@ -17,9 +17,9 @@
 // register file (256 accumulator + 256 vector registers).  The reduction runs in
 // HALF-STEPS of 32 elements.  One half-step needs a STAGE of 32 KiB in LDS: 256
 // activation rows x 64 bytes and two weight half-tiles of 128 rows x 64 bytes.  A
-// ring of kStages stages is kept; the stage of half-step k + kStages - 1 is loaded
+// ring of four stages is kept; the stage of half-step k + 3 is loaded
 // global -> LDS directly (global_load_lds, 16 bytes per lane, no registers in
-// between) while half-step k is computed, so a load has kStages - 2 half-steps to
+// between) while half-step k is computed, so a load has two half-steps to
 // land before anybody waits for it (weights come from HBM, activations from L2).
 // Weight half-tiles are stored in the pages as the exact LDS image, so their copy is
 // linear; activation rows are row-major in HBM and the lane -> chunk choice applies
@@ -67,6 +67,7 @@ constexpr int kRowB = 64;                    // bytes of one row in a stage (32 
 constexpr int kStageA = 256 * kRowB;         // activation part of a stage
 constexpr int kStageBytes = 2 * kStageA;     // + two weight half-tiles of 8 KiB
 constexpr int kHalfTile = 128 * kRowB;       // one weight half-tile
+constexpr int kStages = 4;                   // ring depth: the loop below is unrolled over it
 
 // silu(g) * u with the hardware exp2 and reciprocal (1 ulp each): far below the resolution of
 // the bf16 result; an IEEE division would cost a dozen instructions per element
@@ -89,8 +90,9 @@ __device__ __forceinline__ long long rows_here_tl(int rows) { return (long long)
 // only): 256 rows x 128 columns, wavefront tile 128 x 64, for launches with too few 256-wide tiles
 // to occupy the chip (few rows per expert: the launch is bound by streaming the weights, and more
 // blocks stream more).
-template <int MODE, int S, int NB>
+template <int MODE, int NB>
 __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
+    constexpr int S = kStages;
     static_assert(NB == 2 || (NB == 1 && MODE == 1), "gate/up needs the W1 and the W3 tile");
     constexpr int NS = 2 * NB;                   // 32-column MFMA tiles (B fragments) per wavefront
     constexpr int NMF = 4 * NS;                  // MFMAs per wavefront per 16-wide sub-step
@@ -122,7 +124,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     const int pt0 = nt * NB;
     const int pt1 = (pt0 + 1 < p.n_page_tiles) ? pt0 + 1 : pt0;   // odd tile count: the second half is masked (NB = 2)
     int bad = 0;
-    auto page_addr = [&](int page) -> const char* {
+    auto page_addr = [&](int page) __attribute__((always_inline)) -> const char* {
         int slot = __builtin_amdgcn_readfirstlane(trow[page]);
         if ((unsigned)slot >= (unsigned)p.pool_pages) {   // never follow an entry outside the pool
             bad = 1;
@@ -134,50 +136,57 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     // page-table lookup when the walk crosses a page boundary (once per tiles-per-page k-tiles).
     struct TileWalk {
         int page, within;
-        const char* base;     // address of the current page
+        const char* tile;     // address of the current tile
     };
-    auto walk_start = [&](int first_tile) {
+    auto walk_start = [&](int first_tile) __attribute__((always_inline)) {
         TileWalk w;
         w.page = first_tile / p.tpp;
         w.within = first_tile - w.page * p.tpp;
-        w.base = page_addr(w.page);
+        w.tile = page_addr(w.page) + (int64_t)w.within * 16384;
         return w;
     };
-    auto walk_next = [&](TileWalk& w) {
+    auto walk_next = [&](TileWalk& w) __attribute__((always_inline)) {
+        w.tile += 16384;
         if (++w.within == p.tpp) {
             w.within = 0;
-            w.base = page_addr(++w.page);
+            w.tile = page_addr(++w.page);
         }
     };
     TileWalk w0 = walk_start(pt0 * p.KT), w1 = walk_start(pt1 * p.KT);
 
-    // ---- per-lane sources of the activation rows ------------------------------------
-    // load instruction q = i*4 + wave (i = 0..3) fills LDS rows q*16 .. q*16+15 (1 KiB); lane j
-    // holds row q*16 + j/4 at chunk position j%4, i.e. global chunk (j%4) ^ ((row >> 2) & 3)
-    const char* a_src[4];
+    // ---- sources of the global -> LDS loads: a wave-uniform base that moves along k plus a 32-bit
+    // offset per lane that never changes, so a half-step costs a few scalar additions ----------------
+    // Activation rows: load instruction q = i*4 + wave (i = 0..3) fills LDS rows q*16 .. q*16+15
+    // (1 KiB); lane j holds row q*16 + j/4 at chunk position j%4, i.e. global chunk
+    // (j%4) ^ ((row >> 2) & 3).  Rows past the tail repeat the last row.
+    uint32_t a_off[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int lrow = (i * kWaves + wave) * 16 + (lane >> 2);
-        const int r = min(lrow, rows_here - 1);                               // rows past the tail repeat the last row
+        const int r = min(lrow, rows_here - 1);
         const int c = (lane & 3) ^ ((lrow >> 2) & 3);
-        a_src[i] = p.A + (int64_t)(row0 + r) * p.lda_bytes + c * 16;
+        a_off[i] = (uint32_t)r * (uint32_t)p.lda_bytes + c * 16;
     }
-    const int b_lane_off = wave * 1024 + lane * 16;
+    const char* a_ptr = p.A + (int64_t)row0 * p.lda_bytes;    // + 64 bytes per half-step
+    const uint32_t b_off = wave * 1024 + lane * 16;            // weight half-tiles are copied linearly
 
     // Load instruction i (0..3: activation rows; 4, 5: weight half-tile 0; 6, 7: weight half-tile 1)
-    // of half-step kn into ring slot `slot`.  After the last instruction of an odd half-step the
-    // tile walk moves on.
+    // of half-step kn into ring slot `slot`.  After the last instruction of a half-step the sources
+    // move on (activation rows by 64 bytes, the tile walk after an odd half-step).
     const int KH = 2 * p.KT;
-    auto load_part = [&](int slot, int kn, int i) {
+    auto load_part = [&](int slot, int kn, int odd, int i) __attribute__((always_inline)) {     // odd = kn & 1, known at compile time by the callers
         char* st = smem + slot * kStageBytes;
         if (i < 4) {
-            __builtin_amdgcn_global_load_lds((gptr_t)(a_src[i] + (int64_t)kn * kRowB), (lptr_t)(st + (i * kWaves + wave) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(a_ptr + a_off[i]), (lptr_t)(st + (i * kWaves + wave) * 1024), 16, 0, 0);
         } else {
             const TileWalk& w = i < 6 ? w0 : w1;
             const int part = (i & 1) * (kWaves * 1024);                       // first or second 4 KiB of the half-tile
-            const char* b = w.base + (int64_t)w.within * 16384 + (kn & 1) * kHalfTile + part + b_lane_off;
-            __builtin_amdgcn_global_load_lds((gptr_t)b, (lptr_t)(st + kStageA + (i >= 6 ? kHalfTile : 0) + part + wave * 1024), 16, 0, 0);
-            if (i == kLoadsPerStage - 1 && (kn & 1) && kn + 1 < KH) {
+            const char* b = w.tile + odd * kHalfTile + part;
+            __builtin_amdgcn_global_load_lds((gptr_t)(b + b_off), (lptr_t)(st + kStageA + (i >= 6 ? kHalfTile : 0) + part + wave * 1024), 16, 0, 0);
+        }
+        if (i == kLoadsPerStage - 1) {
+            a_ptr += kRowB;
+            if (odd && kn + 1 < KH) {
                 walk_next(w0);
                 if (NB == 2) walk_next(w1);
             }
@@ -214,18 +223,18 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
 #pragma unroll
         for (int x = 0; x < 8; ++x) fr[1][i][x] = (__bf16)0.f;    // the first rotated MFMA group adds 0 * 0
 
-    auto fetch = [&](const char* st, int ks, int i) {          // i = 0..3: A fragment, 4..: B fragment
+    auto fetch = [&](const char* st, int ks, int i) __attribute__((always_inline)) {          // i = 0..3: A fragment, 4..: B fragment
         const int base = i < 4 ? a_base + i * 32 * kRowB : b_base[i - 4];
         fr[ks][i] = *(const bf16x8*)(st + base + frag_off[ks]);
     };
-    auto mfma = [&](int ks, int j, auto full) {                 // j = 0..NMF-1: MFMA tile (j / NS, j % NS)
+    auto mfma = [&](int ks, int j, auto full) __attribute__((always_inline)) {                 // j = 0..NMF-1: MFMA tile (j / NS, j % NS)
         if (decltype(full)::value || (j / NS) < n_ms)
             acc[j / NS][j % NS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[ks][j / NS], fr[ks][4 + (j % NS)], acc[j / NS][j % NS], 0, 0, 0);
     };
     // One group: the NMF MFMAs of operand set `ms_set`, with the LDS fetches of set `fs_ks` from
     // stage `st` behind the first few of them, two at a time, in the order the next group consumes
     // them, and then `n_loads` global loads, one behind an MFMA (NB = 2: behind every second one).
-    auto group = [&](int ms_set, const char* st, int fs_ks, int nslot, int kn, int first_load, int n_loads, auto full, auto loads_c) {
+    auto group = [&](int ms_set, const char* st, int fs_ks, int nslot, int kn, int odd, int first_load, int n_loads, auto full, auto loads_c) __attribute__((always_inline)) {
         constexpr int order2[8] = {4, 0, 5, 6, 7, 1, 2, 3};
         constexpr int order1[6] = {4, 0, 5, 1, 2, 3};
         constexpr int NR2 = (4 + NS) / 2;        // MFMAs that have fetches behind them
@@ -240,48 +249,54 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
             } else if (decltype(loads_c)::value) {
                 const int li = NB == 2 ? (((j - NR2) & 1) ? (j - NR2 - 1) / 2 : -1) : j - NR2;
                 if (li >= 0 && li < n_loads) {
-                    load_part(nslot, kn, first_load + li);
+                    load_part(nslot, kn, odd, first_load + li);
                     MOE_FENCE();
                 }
             }
         }
     };
 
-    // One half-step.  LOADS: the stage of half-step k + S - 1 is loaded into the slot that
-    // half-step k - 1 used.  WAITN: my loads that may still be in flight when the stage of
-    // half-step k must be complete (the younger stages).
-    int slot = 0;
-    auto half_step = [&](int k, auto full, auto loads_c, auto waitn_c) {
+    // One half-step on ring slot U (a compile-time constant: every LDS address in it is an immediate).
+    // LOADS: the stage of half-step k + S - 1 is loaded into the slot that half-step k - 1 used.
+    // WAITN: my loads that may still be in flight when the stage of half-step k must be complete
+    // (the younger stages).  Operand set U & 1 holds sub-step 0: S is even, so the parity is static too.
+    auto half_step = [&](int k, auto u_c, auto full, auto loads_c, auto waitn_c) __attribute__((always_inline)) {
+        constexpr int U = decltype(u_c)::value;
         wait_loads_and_lds<decltype(waitn_c)::value>();
         __builtin_amdgcn_s_barrier();      // stage k is complete for everyone; nobody reads stage k-1 any more
         asm volatile("" ::: "memory");
-        const char* st = smem + slot * kStageBytes;
-        int nslot = slot + S - 1;
-        if (nslot >= S) nslot -= S;
+        const char* st = smem + U * kStageBytes;
+        constexpr int nslot = (U + S - 1) % S;
         const int kn = k + S - 1;
         MOE_FENCE();
         // group A: MFMAs of (k-1, sub-step 1); fetch (k, sub-step 0); activation-row loads
-        group(1, st, 0, nslot, kn, 0, 4, full, loads_c);
+        group(1, st, 0, nslot, kn, nslot & 1, 0, 4, full, loads_c);
         // group B: MFMAs of (k, sub-step 0); fetch (k, sub-step 1); weight loads
-        group(0, st, 1, nslot, kn, 4, 2 * NB, full, loads_c);
-        if (++slot == S) slot = 0;
+        group(0, st, 1, nslot, kn, nslot & 1, 4, 2 * NB, full, loads_c);
     };
 
-    auto main_loop = [&](auto full) {
-        // prologue: stages 0 .. S-2 in flight (KH >= 4 >= S - 1 always)
+    auto main_loop = [&](auto full) __attribute__((always_inline)) {
+        using std::integral_constant;
+        // prologue: stages 0 .. S-2 in flight (KH is a multiple of 4 and at least 4)
 #pragma unroll
         for (int s = 0; s < S - 1; ++s)
 #pragma unroll
-            for (int i = 0; i < kLoadsPerStage; ++i) load_part(s, s, i);
-        constexpr int kYounger = kLoadsPerStage * (S - 2);
-        const int k_steady = KH - (S - 1);
-        for (int k = 0; k < k_steady; ++k)
-            half_step(k, full, std::true_type{}, std::integral_constant<int, kYounger>{});
-        // drain: no new loads; one stage fewer is in flight in every half-step
-        if (S >= 2) half_step(k_steady, full, std::false_type{}, std::integral_constant<int, kYounger>{});
-        if (S >= 3) half_step(k_steady + 1, full, std::false_type{}, std::integral_constant<int, (S >= 3 ? kLoadsPerStage * (S - 3) : 0)>{});
-        if (S >= 4) half_step(k_steady + 2, full, std::false_type{}, std::integral_constant<int, (S >= 4 ? kLoadsPerStage * (S - 4) : 0)>{});
-        if (S >= 5) half_step(k_steady + 3, full, std::false_type{}, std::integral_constant<int, (S >= 5 ? kLoadsPerStage * (S - 5) : 0)>{});
+            for (int i = 0; i < kLoadsPerStage; ++i) load_part(s, s, s & 1, i);
+        constexpr int kL = kLoadsPerStage;
+        const std::true_type L{};
+        const std::false_type N{};
+        int k = 0;
+        for (; k + S < KH; k += S) {
+            half_step(k, integral_constant<int, 0>{}, full, L, integral_constant<int, 2 * kL>{});
+            half_step(k + 1, integral_constant<int, 1>{}, full, L, integral_constant<int, 2 * kL>{});
+            half_step(k + 2, integral_constant<int, 2>{}, full, L, integral_constant<int, 2 * kL>{});
+            half_step(k + 3, integral_constant<int, 3>{}, full, L, integral_constant<int, 2 * kL>{});
+        }
+        // last four half-steps: one more stage to load, then the ring drains
+        half_step(k, integral_constant<int, 0>{}, full, L, integral_constant<int, 2 * kL>{});
+        half_step(k + 1, integral_constant<int, 1>{}, full, N, integral_constant<int, 2 * kL>{});
+        half_step(k + 2, integral_constant<int, 2>{}, full, N, integral_constant<int, kL>{});
+        half_step(k + 3, integral_constant<int, 3>{}, full, N, integral_constant<int, 0>{});
         // the MFMAs of the last sub-step
         __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
 #pragma unroll
@@ -301,7 +316,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     const bool full_rows = rows_here == BM;
     if (MODE == 0) {
         __bf16* h = (__bf16*)p.out + (int64_t)row0 * p.ldo + nt * 128 + wn * 64 + col_l;
-        auto store_rows = [&](auto full) {
+        auto store_rows = [&](auto full) __attribute__((always_inline)) {
 #pragma unroll
             for (int ms = 0; ms < 4; ++ms)
 #pragma unroll
@@ -326,7 +341,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         const int d0 = nt * (128 * NB) + wn * (32 * NS);   // n_cols is a multiple of 128: with NB = 2 a wavefront's columns are all valid or all not
         if (d0 < p.n_cols) {
             float* o = (float*)p.out + (int64_t)row0 * p.ldo + d0 + col_l;
-            auto store_rows = [&](auto full) {
+            auto store_rows = [&](auto full) __attribute__((always_inline)) {
 #pragma unroll
                 for (int ms = 0; ms < 4; ++ms)
 #pragma unroll
@@ -356,27 +371,18 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     if (bad && tid == 0 && p.status) atomicOr(p.status, 1);
 }
 
-template <int MODE, int S, int NB>
-int launch_mode(const GemmParams& p, int grid, hipStream_t st) {
-    constexpr int lds = S * kStageBytes;
+template <int MODE, int NB>
+int launch_stages(const GemmParams& p, int grid, hipStream_t st) {
+    constexpr int lds = kStages * kStageBytes;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {
-        attr_err = hipFuncSetAttribute((const void*)ffn_gemm_bf16<MODE, S, NB>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr_err = hipFuncSetAttribute((const void*)ffn_gemm_bf16<MODE, NB>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     });
     MOE_HIP_TRY(attr_err);
-    hipLaunchKernelGGL((ffn_gemm_bf16<MODE, S, NB>), dim3(grid), dim3(kThreads), lds, st, p);
+    hipLaunchKernelGGL((ffn_gemm_bf16<MODE, NB>), dim3(grid), dim3(kThreads), lds, st, p);
     MOE_HIP_TRY(hipGetLastError());
     return MOE_OK;
-}
-
-template <int MODE, int NB>
-int launch_stages(const GemmParams& p, int grid, hipStream_t st) {
-    switch (get_opt(OPT_FFN_STAGES)) {
-        case 3: return launch_mode<MODE, 3, NB>(p, grid, st);
-        case 5: return launch_mode<MODE, 5, NB>(p, grid, st);
-        default: return launch_mode<MODE, 4, NB>(p, grid, st);
-    }
 }
 
 }  // namespace

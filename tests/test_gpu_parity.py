@@ -12,7 +12,6 @@ from moe_workloads import CONFIGS, MoEConfig, scaled
 from util import Case, assert_close, assert_h_close, check_permutation_valid, compare_routing, say, shape_of
 
 pytestmark = pytest.mark.gpu
-DEFAULT_STAGES = 4
 
 C1 = CONFIGS["c1_tiny_f32"]
 # reduced bf16 cases: several row tiles of 256 with ragged tails, several column tiles,
@@ -103,18 +102,16 @@ def test_c1_stagewise_and_layer():
 
 
 @pytest.mark.parametrize("name", list(MED))
-@pytest.mark.parametrize("stages,down_cols", [(4, 2), (4, 1), (3, 0), (5, 0)])
-def test_reduced_cases_stagewise_and_layer(name, stages, down_cols):
-    # ring depth of the GEMM pipeline; 256- and 128-wide column tiles of the down projection (0: by grid size)
-    say(f"  case {name} ffn_stages {stages} down_cols {down_cols}")
-    M.set_option("ffn_stages", stages)
+@pytest.mark.parametrize("down_cols", [2, 1, 0])
+def test_reduced_cases_stagewise_and_layer(name, down_cols):
+    # 256- and 128-wide column tiles of the down projection (0: chosen by grid size)
+    say(f"  case {name} down_cols {down_cols}")
     M.set_option("down_cols", down_cols)
     try:
         case = Case(MED[name], shuffle_pages=True, extra_pages=3)
         ref = run_stagewise(case)
         run_layer(case, ref)
     finally:
-        M.set_option("ffn_stages", DEFAULT_STAGES)
         M.set_option("down_cols", 0)
 
 
