@@ -102,9 +102,14 @@ def library_path() -> str:
 def _lib():
     global _LIB
     if _LIB is None:
-        path = os.environ.get("MOE_HIP_LIBRARY", _build.LIB)     # override: an experimental build of the same ABI
-        if not os.path.exists(path):
-            path = _build.build(force=True)          # raises if hipcc is missing or the build fails
+        path = os.environ.get("MOE_HIP_LIBRARY")     # override: an experimental build of the same ABI
+        if path is not None:
+            if not os.path.exists(path):
+                raise FileNotFoundError(f"MOE_HIP_LIBRARY names {path!r}, which does not exist")
+        else:
+            path = _build.LIB
+            if not os.path.exists(path):
+                path = _build.build(force=True)      # raises if hipcc is missing or the build fails
         lib = ctypes.CDLL(path)
         for name, (res, args) in _SIGNATURES.items():
             fn = getattr(lib, name)                   # AttributeError if a declared symbol is missing

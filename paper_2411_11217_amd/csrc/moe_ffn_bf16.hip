@@ -15,18 +15,26 @@
 //
 // Data movement.  256 threads = 4 wavefronts, one per SIMD, each with the full
 // register file (256 accumulator + 256 vector registers).  The reduction runs in
-// HALF-STEPS of 32 elements.  One half-step needs a STAGE of 32 KiB in LDS: 256
-// activation rows x 64 bytes and two weight half-tiles of 128 rows x 64 bytes.  A
-// ring of four stages is kept; the stage of half-step k + 3 is loaded
-// global -> LDS directly (global_load_lds, 16 bytes per lane, no registers in
-// between) while half-step k is computed, so a load has two half-steps to
-// land before anybody waits for it (weights come from HBM, activations from L2).
-// Weight half-tiles are stored in the pages as the exact LDS image, so their copy is
-// linear; activation rows are row-major in HBM and the lane -> chunk choice applies
-// the swizzle.  In LDS the 16-byte chunk c of row r sits at chunk position
-// c ^ ((r >> 2) & 3): 64 banks hold four 64-byte rows, and this makes every 16-lane
-// phase of a ds_read_b128 of an MFMA operand (one row per lane, same chunk) touch
-// each bank once.
+// HALF-STEPS of 32 elements; two of them are a K-STEP (64 elements = one page tile
+// along k).  Operands reach LDS directly (global_load_lds, 16 bytes per lane, no
+// registers in between) through two rings that fill all 160 KiB of the compute unit:
+//   weights:     four stages of 16 KiB, one per half-step: two half-tiles of 128 rows x
+//                64 bytes.  The pages hold the exact LDS image, so the copy is linear.
+//                The stage of half-step k + 3 is loaded while half-step k is computed.
+//   activations: three stages of 32 KiB, one per k-step: 256 rows x 128 bytes, i.e.
+//                one whole cache line per row and load.  Measured: the vector memory
+//                path handles about one cache line per two clocks whether a lane
+//                group uses all 128 bytes of it or only 64, so fetching a row's line
+//                in two halves (a 64-byte stage per half-step, as for the weights)
+//                doubles the time of the activation loads (30 instead of 58 bytes per
+//                clock and compute unit) and made the load path, not the matrix
+//                cores, the longest chain of the loop.  Rows are row-major in HBM; the
+//                lane -> chunk choice of the load applies the swizzle.  The stage of
+//                k-step K + 2 is loaded during the two half-steps of k-step K.
+// Swizzles: in a 64-byte-row stage the 16-byte chunk c of row r sits at position
+// c ^ ((r >> 2) & 3), in a 128-byte-row stage at c ^ ((r >> 1) & 7): 64 banks hold
+// four (two) rows, and this makes every 16-lane phase of a ds_read_b128 of an MFMA
+// operand (one row per lane, same chunk) touch each bank once.
 //
 // Schedule.  Measured on this chip: when all wavefronts issue their loads, then
 // their LDS fetches, then their MFMAs in blocks after each barrier, the matrix
@@ -63,11 +71,15 @@ constexpr int BM = 256;
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
 constexpr int kComputeUnits = 256;           // MI355X
-constexpr int kRowB = 64;                    // bytes of one row in a stage (32 bf16)
-constexpr int kStageA = 256 * kRowB;         // activation part of a stage
-constexpr int kStageBytes = 2 * kStageA;     // + two weight half-tiles of 8 KiB
+constexpr int kRowB = 64;                    // bytes of one weight row in a stage (32 bf16: one half-step)
 constexpr int kHalfTile = 128 * kRowB;       // one weight half-tile
-constexpr int kStages = 4;                   // ring depth: the loop below is unrolled over it
+constexpr int kStageB = 2 * kHalfTile;       // weight stage of one half-step: two half-tiles
+constexpr int kStages = 4;                   // depth of the weight ring: the loop below is unrolled over it
+constexpr int kARowB = 128;                  // bytes of one activation row in a stage (64 bf16: one k-step = two half-steps)
+constexpr int kStageA = 256 * kARowB;        // activation stage of one k-step
+constexpr int kStagesA = 3;                  // depth of the activation ring
+constexpr int kRingA = kStages * kStageB;    // LDS offset of the activation ring (the weight ring sits at 0)
+constexpr int kLdsBytes = kRingA + kStagesA * kStageA;   // 160 KiB: all of a compute unit's LDS
 
 // silu(g) * u with the hardware exp2 and reciprocal (1 ulp each): far below the resolution of
 // the bf16 result; an IEEE division would cost a dozen instructions per element
@@ -114,7 +126,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     const TileCoord tc = locate_tile<BM>(p);
     if (!tc.valid) return;
 #ifdef MOE_FFN_TIMELINE
-    if (tid == 0) { tl[0] = t_entry; tl[5] = wall_clock64(); tl[7] = 1 + rows_here_tl(tc.rows_here); }
+    if (tid == 0) { tl[0] = t_entry; tl[5] = wall_clock64(); tl[7] = 1 + rows_here_tl(tc.rows_here) + ((long long)(__builtin_amdgcn_s_getreg(6164) & 15) << 32); }
 #endif
     MOE_TL(1);
     const int e = tc.e, nt = tc.nt, row0 = tc.row0, rows_here = tc.rows_here;
@@ -156,40 +168,47 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
 
     // ---- sources of the global -> LDS loads: a wave-uniform base that moves along k plus a 32-bit
     // offset per lane that never changes, so a half-step costs a few scalar additions ----------------
-    // Activation rows: load instruction q = i*4 + wave (i = 0..3) fills LDS rows q*16 .. q*16+15
-    // (1 KiB); lane j holds row q*16 + j/4 at chunk position j%4, i.e. global chunk
-    // (j%4) ^ ((row >> 2) & 3).  Rows past the tail repeat the last row.
-    uint32_t a_off[4];
+    // Activation rows are loaded a k-step (128 bytes = one cache line per row) at a time: load
+    // instruction q = i*4 + wave (i = 0..7) fills LDS rows q*8 .. q*8+7 (1 KiB); lane j holds row
+    // q*8 + j/8 at chunk position j%8, i.e. global chunk (j%8) ^ ((row >> 1) & 7).  Rows past the
+    // tail repeat the last row.
+    uint32_t a_off[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int lrow = (i * kWaves + wave) * 16 + (lane >> 2);
+    for (int i = 0; i < 8; ++i) {
+        const int lrow = (i * kWaves + wave) * 8 + (lane >> 3);
         const int r = min(lrow, rows_here - 1);
-        const int c = (lane & 3) ^ ((lrow >> 2) & 3);
+        const int c = (lane & 7) ^ ((lrow >> 1) & 7);
         a_off[i] = (uint32_t)r * (uint32_t)p.lda_bytes + c * 16;
     }
-    const char* a_ptr = p.A + (int64_t)row0 * p.lda_bytes;    // + 64 bytes per half-step
+    const char* a_ptr = p.A + (int64_t)row0 * p.lda_bytes;    // + 128 bytes per k-step
+    int a_wr = kRingA;                                         // LDS offset of the activation stage being filled
     const uint32_t b_off = wave * 1024 + lane * 16;            // weight half-tiles are copied linearly
 
-    // Load instruction i (0..3: activation rows; 4, 5: weight half-tile 0; 6, 7: weight half-tile 1)
-    // of half-step kn into ring slot `slot`.  After the last instruction of a half-step the sources
-    // move on (activation rows by 64 bytes, the tile walk after an odd half-step).
+    // The loads issued during half-step h: activation instructions (h & 1) * 4 + i (i = 0..3) of the
+    // k-step two ahead, and the weight stage of half-step h + 3 (instructions 4, 5: half-tile 0; 6, 7:
+    // half-tile 1) into weight slot `slot`.  After the last instruction of a kind the sources move on.
     const int KH = 2 * p.KT;
-    auto load_part = [&](int slot, int kn, int odd, int i) __attribute__((always_inline)) {     // odd = kn & 1, known at compile time by the callers
-        char* st = smem + slot * kStageBytes;
-        if (i < 4) {
-            __builtin_amdgcn_global_load_lds((gptr_t)(a_ptr + a_off[i]), (lptr_t)(st + (i * kWaves + wave) * 1024), 16, 0, 0);
-        } else {
-            const TileWalk& w = i < 6 ? w0 : w1;
-            const int part = (i & 1) * (kWaves * 1024);                       // first or second 4 KiB of the half-tile
-            const char* b = w.tile + odd * kHalfTile + part;
-            __builtin_amdgcn_global_load_lds((gptr_t)(b + b_off), (lptr_t)(st + kStageA + (i >= 6 ? kHalfTile : 0) + part + wave * 1024), 16, 0, 0);
+    auto load_a = [&](int part, int i) __attribute__((always_inline)) {
+        const int ia = part * 4 + i;
+#ifndef MOE_FFN_NO_LOADS
+        __builtin_amdgcn_global_load_lds((gptr_t)(a_ptr + a_off[ia]), (lptr_t)(smem + a_wr + (ia * kWaves + wave) * 1024), 16, 0, 0);
+#endif
+        if (ia == 7) {
+            a_ptr += kARowB;
+            a_wr = (a_wr == kRingA + (kStagesA - 1) * kStageA) ? kRingA : a_wr + kStageA;
         }
-        if (i == kLoadsPerStage - 1) {
-            a_ptr += kRowB;
-            if (odd && kn + 1 < KH) {
-                walk_next(w0);
-                if (NB == 2) walk_next(w1);
-            }
+    };
+    auto load_b = [&](int slot, int kn, int odd, int i) __attribute__((always_inline)) {     // odd = kn & 1, known at compile time by the callers
+        char* st = smem + slot * kStageB;
+        const TileWalk& w = i < 2 ? w0 : w1;
+        const int part = (i & 1) * (kWaves * 1024);                       // first or second 4 KiB of the half-tile
+        const char* b = w.tile + odd * kHalfTile + part;
+#ifndef MOE_FFN_NO_LOADS
+        __builtin_amdgcn_global_load_lds((gptr_t)(b + b_off), (lptr_t)(st + (i >= 2 ? kHalfTile : 0) + part + wave * 1024), 16, 0, 0);
+#endif
+        if (i == 2 * NB - 1 && odd && kn + 1 < KH) {
+            walk_next(w0);
+            if (NB == 2) walk_next(w1);
         }
     };
 
@@ -201,18 +220,25 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // LDS byte offset of this lane's operand chunk for sub-step ks (0, 1), relative to the first
-    // row of a 32-row MFMA tile: row lane%32, chunk 2*ks + lane/32, swizzled
+    // LDS byte offsets of this lane's operand chunks.  Weights (64-byte rows, one half-step per stage):
+    // sub-step ks (0, 1) reads row lane%32, chunk 2*ks + lane/32, swizzled.  Activations (128-byte rows,
+    // two half-steps per stage): half-step parity hp and sub-step ks read chunk 4*hp + 2*ks + lane/32.
     const int c0 = (lane >> 5) ^ ((lane >> 2) & 3);
     const int lane_row = (lane & 31) * kRowB;
     const int frag_off[2] = {lane_row + (c0 << 4), lane_row + ((c0 ^ 2) << 4)};
-    const int a_base = wm * 128 * kRowB;
+    int a_frag[2][2];                 // includes the activation stage being read: moves on after every odd half-step
+#pragma unroll
+    for (int hp = 0; hp < 2; ++hp)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+            a_frag[hp][ks] = kRingA + wm * 128 * kARowB + (lane & 31) * kARowB + (((4 * hp + 2 * ks + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
+    int a_rd = 0;                     // activation stage being read
     // B fragment ns: MODE 0: gate rows wn*64 + {0, 32} of tile 0, then the same up rows of tile 1;
     //                MODE 1: rows wn*(32*NS) + ns*32 of the 128*NB rows of the block's tiles
     int b_base[NS];
 #pragma unroll
     for (int ns = 0; ns < NS; ++ns)
-        b_base[ns] = kStageA + ((MODE == 0) ? (ns >> 1) * 128 + wn * 64 + (ns & 1) * 32 : wn * (32 * NS) + ns * 32) * kRowB;
+        b_base[ns] = ((MODE == 0) ? (ns >> 1) * 128 + wn * 64 + (ns & 1) * 32 : wn * (32 * NS) + ns * 32) * kRowB;
     // 32-row MFMA tiles of this wavefront that hold at least one valid row
     const int n_ms = max(0, min(4, (rows_here - wm * 128 + 31) >> 5));
 
@@ -223,80 +249,110 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
 #pragma unroll
         for (int x = 0; x < 8; ++x) fr[1][i][x] = (__bf16)0.f;    // the first rotated MFMA group adds 0 * 0
 
-    auto fetch = [&](const char* st, int ks, int i) __attribute__((always_inline)) {          // i = 0..3: A fragment, 4..: B fragment
-        const int base = i < 4 ? a_base + i * 32 * kRowB : b_base[i - 4];
-        fr[ks][i] = *(const bf16x8*)(st + base + frag_off[ks]);
+    auto fetch = [&](const char* st, int hp, int ks, int i) __attribute__((always_inline)) {  // i = 0..3: A fragment, 4..: B fragment; st: weight stage
+        if (i < 4) fr[ks][i] = *(const bf16x8*)(smem + a_frag[hp][ks] + i * 32 * kARowB);
+        else fr[ks][i] = *(const bf16x8*)(st + b_base[i - 4] + frag_off[ks]);
     };
     auto mfma = [&](int ks, int j, auto full) __attribute__((always_inline)) {                 // j = 0..NMF-1: MFMA tile (j / NS, j % NS)
+#ifdef MOE_FFN_NO_MFMA     // experiment builds only
+        {
+            typedef int i32x4_t __attribute__((ext_vector_type(4)));
+            const bf16x8 fa = fr[ks][j / NS], fb = fr[ks][4 + (j % NS)];
+            i32x4_t ia, ib;
+            __builtin_memcpy(&ia, &fa, 16);
+            __builtin_memcpy(&ib, &fb, 16);
+            asm volatile("" ::"v"(ia), "v"(ib));
+        }
+#else
         if (decltype(full)::value || (j / NS) < n_ms)
             acc[j / NS][j % NS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[ks][j / NS], fr[ks][4 + (j % NS)], acc[j / NS][j % NS], 0, 0, 0);
+#endif
     };
-    // One group: the NMF MFMAs of operand set `ms_set`, with the LDS fetches of set `fs_ks` from
-    // stage `st` behind the first few of them, two at a time, in the order the next group consumes
-    // them, and then `n_loads` global loads, one behind an MFMA (NB = 2: behind every second one).
-    auto group = [&](int ms_set, const char* st, int fs_ks, int nslot, int kn, int odd, int first_load, int n_loads, auto full, auto loads_c) __attribute__((always_inline)) {
+    // One group: the NMF MFMAs of operand set `ms_set`, with the LDS fetches of set `fs_ks` (weights
+    // from stage `st`) behind the first few of them, two at a time, in the order the next group
+    // consumes them, and then global loads, one behind an MFMA (NB = 2: behind every second one):
+    // KIND 1 the four activation loads of `part`, KIND 2 the 2 * NB weight loads, KIND 0 none.
+    auto group = [&](int ms_set, const char* st, int hp, int fs_ks, auto kind_c, int part, int nslot, int kn, auto full) __attribute__((always_inline)) {
+        constexpr int KIND = decltype(kind_c)::value;
         constexpr int order2[8] = {4, 0, 5, 6, 7, 1, 2, 3};
         constexpr int order1[6] = {4, 0, 5, 1, 2, 3};
         constexpr int NR2 = (4 + NS) / 2;        // MFMAs that have fetches behind them
+        constexpr int n_loads = KIND == 1 ? 4 : 2 * NB;
 #pragma unroll
         for (int j = 0; j < NMF; ++j) {
             mfma(ms_set, j, full);
             MOE_FENCE();
             if (j < NR2) {
-                fetch(st, fs_ks, NB == 2 ? order2[2 * j] : order1[2 * j]);
-                fetch(st, fs_ks, NB == 2 ? order2[2 * j + 1] : order1[2 * j + 1]);
+                fetch(st, hp, fs_ks, NB == 2 ? order2[2 * j] : order1[2 * j]);
+                fetch(st, hp, fs_ks, NB == 2 ? order2[2 * j + 1] : order1[2 * j + 1]);
                 MOE_FENCE();
-            } else if (decltype(loads_c)::value) {
+            } else if (KIND != 0) {
                 const int li = NB == 2 ? (((j - NR2) & 1) ? (j - NR2 - 1) / 2 : -1) : j - NR2;
                 if (li >= 0 && li < n_loads) {
-                    load_part(nslot, kn, odd, first_load + li);
+                    if (KIND == 1) load_a(part, li);
+                    else load_b(nslot, kn, nslot & 1, li);
                     MOE_FENCE();
                 }
             }
         }
     };
 
-    // One half-step on ring slot U (a compile-time constant: every LDS address in it is an immediate).
-    // LOADS: the stage of half-step k + S - 1 is loaded into the slot that half-step k - 1 used.
-    // WAITN: my loads that may still be in flight when the stage of half-step k must be complete
-    // (the younger stages).  Operand set U & 1 holds sub-step 0: S is even, so the parity is static too.
-    auto half_step = [&](int k, auto u_c, auto full, auto loads_c, auto waitn_c) __attribute__((always_inline)) {
+    // One half-step on weight-ring slot U (a compile-time constant: every weight address in LDS is an
+    // immediate; the activation stage moves through per-lane offsets).  LA / LB: issue the activation /
+    // weight loads of this half-step.  WAITN: my loads that may still be in flight when the stages of
+    // half-step k must be complete (those issued during the two half-steps before).  Operand set U & 1
+    // holds sub-step 0: S is even, so the parity of k is static too.
+    auto half_step = [&](int k, auto u_c, auto full, auto la_c, auto lb_c, auto waitn_c) __attribute__((always_inline)) {
+        using std::integral_constant;
         constexpr int U = decltype(u_c)::value;
+        constexpr int HP = U & 1;
         wait_loads_and_lds<decltype(waitn_c)::value>();
-        __builtin_amdgcn_s_barrier();      // stage k is complete for everyone; nobody reads stage k-1 any more
+        __builtin_amdgcn_s_barrier();      // the stages of k are complete for everyone; nobody reads those of k-1 any more
         asm volatile("" ::: "memory");
-        const char* st = smem + U * kStageBytes;
+        const char* st = smem + U * kStageB;
         constexpr int nslot = (U + S - 1) % S;
         const int kn = k + S - 1;
         MOE_FENCE();
         // group A: MFMAs of (k-1, sub-step 1); fetch (k, sub-step 0); activation-row loads
-        group(1, st, 0, nslot, kn, nslot & 1, 0, 4, full, loads_c);
+        group(1, st, HP, 0, integral_constant<int, decltype(la_c)::value ? 1 : 0>{}, HP, nslot, kn, full);
         // group B: MFMAs of (k, sub-step 0); fetch (k, sub-step 1); weight loads
-        group(0, st, 1, nslot, kn, nslot & 1, 4, 2 * NB, full, loads_c);
+        group(0, st, HP, 1, integral_constant<int, decltype(lb_c)::value ? 2 : 0>{}, HP, nslot, kn, full);
+        if (HP) {                          // the next half-step reads the next activation stage
+            const int d = (a_rd == kStagesA - 1) ? -(kStagesA - 1) * kStageA : kStageA;
+            a_rd = (a_rd == kStagesA - 1) ? 0 : a_rd + 1;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) a_frag[x >> 1][x & 1] += d;
+        }
     };
 
     auto main_loop = [&](auto full) __attribute__((always_inline)) {
         using std::integral_constant;
-        // prologue: stages 0 .. S-2 in flight (KH is a multiple of 4 and at least 4)
-#pragma unroll
-        for (int s = 0; s < S - 1; ++s)
-#pragma unroll
-            for (int i = 0; i < kLoadsPerStage; ++i) load_part(s, s, s & 1, i);
         constexpr int kL = kLoadsPerStage;
         const std::true_type L{};
         const std::false_type N{};
+        // prologue, in the order the half-steps -4 .. -1 would have issued them: activation k-steps
+        // 0 and 1, weight half-steps 0 .. 2 (KH is a multiple of 4 and at least 4)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) load_a(0, i);
+#pragma unroll
+        for (int s = 0; s < S - 1; ++s) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) load_a((s + 1) & 1, i);
+#pragma unroll
+            for (int i = 0; i < 2 * NB; ++i) load_b(s, s, s & 1, i);
+        }
         int k = 0;
         for (; k + S < KH; k += S) {
-            half_step(k, integral_constant<int, 0>{}, full, L, integral_constant<int, 2 * kL>{});
-            half_step(k + 1, integral_constant<int, 1>{}, full, L, integral_constant<int, 2 * kL>{});
-            half_step(k + 2, integral_constant<int, 2>{}, full, L, integral_constant<int, 2 * kL>{});
-            half_step(k + 3, integral_constant<int, 3>{}, full, L, integral_constant<int, 2 * kL>{});
+            half_step(k, integral_constant<int, 0>{}, full, L, L, integral_constant<int, 2 * kL>{});
+            half_step(k + 1, integral_constant<int, 1>{}, full, L, L, integral_constant<int, 2 * kL>{});
+            half_step(k + 2, integral_constant<int, 2>{}, full, L, L, integral_constant<int, 2 * kL>{});
+            half_step(k + 3, integral_constant<int, 3>{}, full, L, L, integral_constant<int, 2 * kL>{});
         }
-        // last four half-steps: one more stage to load, then the ring drains
-        half_step(k, integral_constant<int, 0>{}, full, L, integral_constant<int, 2 * kL>{});
-        half_step(k + 1, integral_constant<int, 1>{}, full, N, integral_constant<int, 2 * kL>{});
-        half_step(k + 2, integral_constant<int, 2>{}, full, N, integral_constant<int, kL>{});
-        half_step(k + 3, integral_constant<int, 3>{}, full, N, integral_constant<int, 0>{});
+        // last four half-steps: one more weight stage to load, then the rings drain
+        half_step(k, integral_constant<int, 0>{}, full, N, L, integral_constant<int, 2 * kL>{});
+        half_step(k + 1, integral_constant<int, 1>{}, full, N, N, integral_constant<int, kL + 2 * NB>{});
+        half_step(k + 2, integral_constant<int, 2>{}, full, N, N, integral_constant<int, 2 * NB>{});
+        half_step(k + 3, integral_constant<int, 3>{}, full, N, N, integral_constant<int, 0>{});
         // the MFMAs of the last sub-step
         __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
 #pragma unroll
@@ -373,7 +429,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
 
 template <int MODE, int NB>
 int launch_stages(const GemmParams& p, int grid, hipStream_t st) {
-    constexpr int lds = kStages * kStageBytes;
+    constexpr int lds = kLdsBytes;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {
