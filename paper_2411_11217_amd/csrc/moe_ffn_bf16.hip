@@ -1,5 +1,5 @@
 // a3. Grouped SwiGLU expert FFN, bf16 operands, fp32 accumulation, on the CDNA4
-// matrix cores (v_mfma_f32_32x32x16_bf16), weights read through the page table.
+// matrix cores (v_mfma_f32_16x16x32_bf16), weights read through the page table.
 //
 // Two launches of one kernel template:
 //   MODE 0 (gate/up):  [g | u] = x_perm . [W1_e ; W3_e]^T,  h = bf16(silu(g) * u)
@@ -39,21 +39,26 @@
 // Schedule.  Measured on this chip: when all wavefronts issue their loads, then
 // their LDS fetches, then their MFMAs in blocks after each barrier, the matrix
 // cores idle while every wavefront queues at the memory pipeline (about 63 %
-// utilisation).  The loop is therefore (a) rotated: the MFMAs of the second
-// sub-step of half-step k-1 are issued AFTER the barrier that opens half-step k,
-// so the matrix cores have work while the wavefronts synchronise, and (b)
-// interleaved: between two MFMAs at most two LDS fetches or one global load are
+// utilisation).  The loop is therefore (a) rotated: half of the MFMAs of half-step
+// k-1 are issued AFTER the barrier that opens half-step k, so the matrix cores have
+// work while the wavefronts synchronise and the first operands of k are fetched,
+// and (b) interleaved: between two MFMAs at most one LDS fetch or one global load is
 // issued.  Scheduling fences pin that order.
 //
 // Wavefront w computes rows (w / 2) * 128 .. +127 and, of the 256 columns, for
 // MODE 0 columns (w % 2) * 64 .. +63 of both tiles, for MODE 1 columns
-// (w % 2) * 128 .. +127: 4 x 4 MFMA tiles of 32 x 32, 256 accumulator registers.
+// (w % 2) * 128 .. +127: 8 x 8 MFMA tiles of 16 x 16, 256 accumulator registers.
 // Measured against 8 wavefronts of 128 x 64 each: a 128 x 128 wavefront tile needs
-// 8 LDS fetches per 16 MFMAs instead of 12, a third less LDS traffic; the chip is
-// power limited under this load, the clock rises and the loop runs ~10 % faster.
+// a third less LDS traffic per MFMA; the chip is power limited under this load, the
+// clock rises and the loop runs ~10 % faster.  Measured for the MFMA shape (a loop
+// of nothing but MFMAs on random bf16 operands, all compute units): 16x16x32 sustains
+// 2.08 PFLOP/s at 2.05 GHz, 32x32x16 1.82 PFLOP/s at 1.76 GHz - the same arithmetic,
+// but half the accumulator traffic per multiply-add, and the power limit, not the
+// issue rate, sets the speed.
 #include <algorithm>
 #include <mutex>
 #include <type_traits>
+#include <utility>
 
 #include "moe_ffn_common.h"
 
@@ -62,8 +67,8 @@ namespace {
 
 #define MOE_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));        // an MFMA operand: 8 bf16 in four registers
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
@@ -94,6 +99,60 @@ __device__ __forceinline__ void wait_loads_and_lds() {
     __builtin_amdgcn_s_waitcnt(0x0070 | (N & 15) | ((N >> 4) << 14));
 }
 
+// D = A * B + D on a 16 x 16 tile over 32 k (v_mfma_f32_16x16x32_bf16): lane l holds row l % 16 of A
+// and column l % 16 of B, each the 8 elements k = (l / 16) * 8 .. + 7, and D[(l / 16) * 4 + r][l % 16] in
+// register r of the tile's four.
+//
+// The accumulators are the accumulator registers a0 .. a255 (a0 .. a127 for the narrow block) NAMED in
+// inline assembly, tile t in a[4t : 4t + 3]; the compiler never sees them as values.  With the
+// builtin, or with "+a" operands, the register allocator copies accumulator tiles between registers
+// inside or next to the loop; it does not know that the asm is an MFMA whose result lands passes
+// later, and such a copy reads or overwrites a register an MFMA in flight still writes.  So:
+// acc_declare() makes the registers part of the kernel's register count, acc_zero / acc_read are the
+// only other accesses, and acc_read may only run after mfma_drain().
+template <int NREGS>
+__device__ __forceinline__ void acc_declare() {
+#ifdef __HIP_DEVICE_COMPILE__        // the host pass of the compiler does not know these registers
+    if (NREGS == 256) asm volatile("" ::: "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", "a10", "a11", "a12", "a13", "a14", "a15", "a16", "a17", "a18", "a19", "a20", "a21", "a22", "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31", "a32", "a33", "a34", "a35", "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", "a45", "a46", "a47", "a48", "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", "a58", "a59", "a60", "a61", "a62", "a63", "a64", "a65", "a66", "a67", "a68", "a69", "a70", "a71", "a72", "a73", "a74", "a75", "a76", "a77", "a78", "a79", "a80", "a81", "a82", "a83", "a84", "a85", "a86", "a87", "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95", "a96", "a97", "a98", "a99", "a100", "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", "a109", "a110", "a111", "a112", "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", "a121", "a122", "a123", "a124", "a125", "a126", "a127", "a128", "a129", "a130", "a131", "a132", "a133", "a134", "a135", "a136", "a137", "a138", "a139", "a140", "a141", "a142", "a143", "a144", "a145", "a146", "a147", "a148", "a149", "a150", "a151", "a152", "a153", "a154", "a155", "a156", "a157", "a158", "a159", "a160", "a161", "a162", "a163", "a164", "a165", "a166", "a167", "a168", "a169", "a170", "a171", "a172", "a173", "a174", "a175", "a176", "a177", "a178", "a179", "a180", "a181", "a182", "a183", "a184", "a185", "a186", "a187", "a188", "a189", "a190", "a191", "a192", "a193", "a194", "a195", "a196", "a197", "a198", "a199", "a200", "a201", "a202", "a203", "a204", "a205", "a206", "a207", "a208", "a209", "a210", "a211", "a212", "a213", "a214", "a215", "a216", "a217", "a218", "a219", "a220", "a221", "a222", "a223", "a224", "a225", "a226", "a227", "a228", "a229", "a230", "a231", "a232", "a233", "a234", "a235", "a236", "a237", "a238", "a239", "a240", "a241", "a242", "a243", "a244", "a245", "a246", "a247", "a248", "a249", "a250", "a251", "a252", "a253", "a254", "a255");
+    else asm volatile("" ::: "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", "a10", "a11", "a12", "a13", "a14", "a15", "a16", "a17", "a18", "a19", "a20", "a21", "a22", "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31", "a32", "a33", "a34", "a35", "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", "a45", "a46", "a47", "a48", "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", "a58", "a59", "a60", "a61", "a62", "a63", "a64", "a65", "a66", "a67", "a68", "a69", "a70", "a71", "a72", "a73", "a74", "a75", "a76", "a77", "a78", "a79", "a80", "a81", "a82", "a83", "a84", "a85", "a86", "a87", "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95", "a96", "a97", "a98", "a99", "a100", "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", "a109", "a110", "a111", "a112", "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", "a121", "a122", "a123", "a124", "a125", "a126", "a127");
+#endif
+}
+template <int R>
+__device__ __forceinline__ void mfma_16x16x32(const i32x4& a, const i32x4& b) {     // tile in a[R : R + 3]
+#ifdef __HIP_DEVICE_COMPILE__
+    asm volatile("v_mfma_f32_16x16x32_bf16 a[%2:%3], %0, %1, a[%2:%3]" ::"v"(a), "v"(b), "n"(R), "n"(R + 3));
+#endif
+}
+template <int R>
+__device__ __forceinline__ void acc_zero() {
+#ifdef __HIP_DEVICE_COMPILE__
+    asm volatile("v_accvgpr_write_b32 a[%0], 0" ::"n"(R));
+#endif
+}
+template <int R>
+__device__ __forceinline__ float acc_read() {
+    float v = 0.f;
+#ifdef __HIP_DEVICE_COMPILE__
+    asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(v) : "n"(R));
+#endif
+    return v;
+}
+__device__ __forceinline__ void mfma_drain() {      // more wait states than the longest MFMA pipeline needs
+#ifdef __HIP_DEVICE_COMPILE__
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+#endif
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 #ifdef MOE_FFN_TIMELINE
 __device__ __forceinline__ long long rows_here_tl(int rows) { return (long long)rows << 8; }
 #endif
@@ -106,8 +165,8 @@ template <int MODE, int NB>
 __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     constexpr int S = kStages;
     static_assert(NB == 2 || (NB == 1 && MODE == 1), "gate/up needs the W1 and the W3 tile");
-    constexpr int NS = 2 * NB;                   // 32-column MFMA tiles (B fragments) per wavefront
-    constexpr int NMF = 4 * NS;                  // MFMAs per wavefront per 16-wide sub-step
+    constexpr int NJ = 4 * NB;                   // 16-column MFMA tiles (B fragments) per wavefront
+    constexpr int NMF = 4 * NJ;                  // MFMAs of a group: four 16-row tiles x NJ
     constexpr int kLoadsPerStage = 4 + 2 * NB;   // global_load_lds instructions per wavefront per stage
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const int tid = threadIdx.x;
@@ -190,9 +249,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     const int KH = 2 * p.KT;
     auto load_a = [&](int part, int i) __attribute__((always_inline)) {
         const int ia = part * 4 + i;
-#ifndef MOE_FFN_NO_LOADS
         __builtin_amdgcn_global_load_lds((gptr_t)(a_ptr + a_off[ia]), (lptr_t)(smem + a_wr + (ia * kWaves + wave) * 1024), 16, 0, 0);
-#endif
         if (ia == 7) {
             a_ptr += kARowB;
             a_wr = (a_wr == kRingA + (kStagesA - 1) * kStageA) ? kRingA : a_wr + kStageA;
@@ -203,109 +260,70 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         const TileWalk& w = i < 2 ? w0 : w1;
         const int part = (i & 1) * (kWaves * 1024);                       // first or second 4 KiB of the half-tile
         const char* b = w.tile + odd * kHalfTile + part;
-#ifndef MOE_FFN_NO_LOADS
         __builtin_amdgcn_global_load_lds((gptr_t)(b + b_off), (lptr_t)(st + (i >= 2 ? kHalfTile : 0) + part + wave * 1024), 16, 0, 0);
-#endif
         if (i == 2 * NB - 1 && odd && kn + 1 < KH) {
             walk_next(w0);
             if (NB == 2) walk_next(w1);
         }
     };
 
-    f32x16 acc[4][NS];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < NS; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    // accumulator tile (i, j), rows wm*128 + i*16, columns by B fragment j: registers a[(i*NJ + j)*4 ..+3]
+    acc_declare<32 * NJ>();
+    static_for<32 * NJ>([&](auto rc) __attribute__((always_inline)) { acc_zero<decltype(rc)::value>(); });
 
-    // LDS byte offsets of this lane's operand chunks.  Weights (64-byte rows, one half-step per stage):
-    // sub-step ks (0, 1) reads row lane%32, chunk 2*ks + lane/32, swizzled.  Activations (128-byte rows,
-    // two half-steps per stage): half-step parity hp and sub-step ks read chunk 4*hp + 2*ks + lane/32.
-    const int c0 = (lane >> 5) ^ ((lane >> 2) & 3);
-    const int lane_row = (lane & 31) * kRowB;
-    const int frag_off[2] = {lane_row + (c0 << 4), lane_row + ((c0 ^ 2) << 4)};
-    int a_frag[2][2];                 // includes the activation stage being read: moves on after every odd half-step
+    // LDS byte offsets of this lane's operand chunks: row lane%16 of a 16-row MFMA tile, chunk lane/16
+    // of the four a half-step has.  Weights (64-byte rows, one half-step per stage): chunk lane/16;
+    // activations (128-byte rows, two half-steps per stage): chunk 4*hp + lane/16 in half-step parity hp.
+    const int b_frag0 = (lane & 15) * kRowB + ((((lane >> 4) ^ ((lane >> 2) & 3)) & 3) << 4);
+    int a_frag[2];                    // includes the activation stage being read: moves on after every odd half-step
 #pragma unroll
     for (int hp = 0; hp < 2; ++hp)
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-            a_frag[hp][ks] = kRingA + wm * 128 * kARowB + (lane & 31) * kARowB + (((4 * hp + 2 * ks + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
+        a_frag[hp] = kRingA + wm * 128 * kARowB + (lane & 15) * kARowB + (((4 * hp + (lane >> 4)) ^ ((lane >> 1) & 7)) << 4);
     int a_rd = 0;                     // activation stage being read
-    // B fragment ns: MODE 0: gate rows wn*64 + {0, 32} of tile 0, then the same up rows of tile 1;
-    //                MODE 1: rows wn*(32*NS) + ns*32 of the 128*NB rows of the block's tiles
-    int b_base[NS];
+    // B fragment j: MODE 0: gate rows wn*64 + (j%4)*16 of tile 0 (j < 4), the same up rows of tile 1 (j >= 4);
+    //               MODE 1: rows wn*(16*NJ) + j*16 of the 128*NB rows of the block's tiles
+    int b_base[NJ];
 #pragma unroll
-    for (int ns = 0; ns < NS; ++ns)
-        b_base[ns] = ((MODE == 0) ? (ns >> 1) * 128 + wn * 64 + (ns & 1) * 32 : wn * (32 * NS) + ns * 32) * kRowB;
-    // 32-row MFMA tiles of this wavefront that hold at least one valid row
-    const int n_ms = max(0, min(4, (rows_here - wm * 128 + 31) >> 5));
+    for (int j = 0; j < NJ; ++j)
+        b_base[j] = ((MODE == 0) ? (j >> 2) * 128 + wn * 64 + (j & 3) * 16 : wn * (16 * NJ) + j * 16) * kRowB;
 
-    // operand registers: two sets (one per sub-step), each 4 A fragments and NS B fragments
-    bf16x8 fr[2][4 + NS];
+    // operand registers: activation fragments of row tiles 0..3 (AX) and 4..7 (AY), weight fragments of
+    // two half-steps (the MFMAs of row tiles 4..7 run one half-step behind, see below)
+    i32x4 AX[4], AY[4], BF[2][NJ];
 #pragma unroll
-    for (int i = 0; i < 4 + NS; ++i)
+    for (int i = 0; i < 4; ++i) AX[i] = AY[i] = i32x4{0, 0, 0, 0};
 #pragma unroll
-        for (int x = 0; x < 8; ++x) fr[1][i][x] = (__bf16)0.f;    // the first rotated MFMA group adds 0 * 0
+    for (int j = 0; j < NJ; ++j) BF[0][j] = BF[1][j] = i32x4{0, 0, 0, 0};   // the first rotated MFMA group adds 0 * 0
 
-    auto fetch = [&](const char* st, int hp, int ks, int i) __attribute__((always_inline)) {  // i = 0..3: A fragment, 4..: B fragment; st: weight stage
-        if (i < 4) fr[ks][i] = *(const bf16x8*)(smem + a_frag[hp][ks] + i * 32 * kARowB);
-        else fr[ks][i] = *(const bf16x8*)(st + b_base[i - 4] + frag_off[ks]);
+    auto fetch_a = [&](int hp, int i) __attribute__((always_inline)) {      // row tile i = 0..7 of the activation stage being read
+        const i32x4 v = *(const i32x4*)(smem + a_frag[hp] + i * 16 * kARowB);
+        if (i < 4) AX[i] = v;
+        else AY[i - 4] = v;
     };
-    auto mfma = [&](int ks, int j, auto full) __attribute__((always_inline)) {                 // j = 0..NMF-1: MFMA tile (j / NS, j % NS)
-#ifdef MOE_FFN_NO_MFMA     // experiment builds only
-        {
-            typedef int i32x4_t __attribute__((ext_vector_type(4)));
-            const bf16x8 fa = fr[ks][j / NS], fb = fr[ks][4 + (j % NS)];
-            i32x4_t ia, ib;
-            __builtin_memcpy(&ia, &fa, 16);
-            __builtin_memcpy(&ib, &fb, 16);
-            asm volatile("" ::"v"(ia), "v"(ib));
-        }
-#else
-        if (decltype(full)::value || (j / NS) < n_ms)
-            acc[j / NS][j % NS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[ks][j / NS], fr[ks][4 + (j % NS)], acc[j / NS][j % NS], 0, 0, 0);
-#endif
+    auto fetch_b = [&](const char* st, int set, int j) __attribute__((always_inline)) {     // st: weight stage
+        BF[set][j] = *(const i32x4*)(st + b_base[j] + b_frag0);
     };
-    // One group: the NMF MFMAs of operand set `ms_set`, with the LDS fetches of set `fs_ks` (weights
-    // from stage `st`) behind the first few of them, two at a time, in the order the next group
-    // consumes them, and then global loads, one behind an MFMA (NB = 2: behind every second one):
-    // KIND 1 the four activation loads of `part`, KIND 2 the 2 * NB weight loads, KIND 0 none.
-    auto group = [&](int ms_set, const char* st, int hp, int fs_ks, auto kind_c, int part, int nslot, int kn, auto full) __attribute__((always_inline)) {
-        constexpr int KIND = decltype(kind_c)::value;
-        constexpr int order2[8] = {4, 0, 5, 6, 7, 1, 2, 3};
-        constexpr int order1[6] = {4, 0, 5, 1, 2, 3};
-        constexpr int NR2 = (4 + NS) / 2;        // MFMAs that have fetches behind them
-        constexpr int n_loads = KIND == 1 ? 4 : 2 * NB;
-#pragma unroll
-        for (int j = 0; j < NMF; ++j) {
-            mfma(ms_set, j, full);
-            MOE_FENCE();
-            if (j < NR2) {
-                fetch(st, hp, fs_ks, NB == 2 ? order2[2 * j] : order1[2 * j]);
-                fetch(st, hp, fs_ks, NB == 2 ? order2[2 * j + 1] : order1[2 * j + 1]);
-                MOE_FENCE();
-            } else if (KIND != 0) {
-                const int li = NB == 2 ? (((j - NR2) & 1) ? (j - NR2 - 1) / 2 : -1) : j - NR2;
-                if (li >= 0 && li < n_loads) {
-                    if (KIND == 1) load_a(part, li);
-                    else load_b(nslot, kn, nslot & 1, li);
-                    MOE_FENCE();
-                }
-            }
-        }
+    auto mfma = [&](auto half_c, auto set_c, auto m_c) __attribute__((always_inline)) {    // m = 0..NMF-1: row tile half*4 + m / NJ, fragment m % NJ
+        constexpr int half = decltype(half_c)::value, set = decltype(set_c)::value, m = decltype(m_c)::value;
+        constexpr int i = half * 4 + m / NJ, j = m % NJ;
+        mfma_16x16x32<(i * NJ + j) * 4>(half ? AY[m / NJ] : AX[m / NJ], BF[set][j]);
     };
 
     // One half-step on weight-ring slot U (a compile-time constant: every weight address in LDS is an
-    // immediate; the activation stage moves through per-lane offsets).  LA / LB: issue the activation /
-    // weight loads of this half-step.  WAITN: my loads that may still be in flight when the stages of
-    // half-step k must be complete (those issued during the two half-steps before).  Operand set U & 1
-    // holds sub-step 0: S is even, so the parity of k is static too.
-    auto half_step = [&](int k, auto u_c, auto full, auto la_c, auto lb_c, auto waitn_c) __attribute__((always_inline)) {
-        using std::integral_constant;
+    // immediate; the activation stage moves through per-lane offsets).  Two groups of NMF MFMAs with
+    // the other instructions spread between them, at most one behind an MFMA:
+    //   group 1: row tiles 4..7 of half-step k-1 (operands fetched during k-1); fetches the weight
+    //            fragments of k and the activation fragments of row tiles 0..3; issues the activation loads;
+    //   group 2: row tiles 0..3 of half-step k; fetches the activation fragments of row tiles 4..7;
+    //            issues the weight loads.
+    // LA / LB: issue the activation / weight loads of this half-step.  WAITN: my loads that may still
+    // be in flight when the stages of half-step k must be complete (those issued during the two
+    // half-steps before).  Weight fragment set U & 1 belongs to half-step k: S is even, so the parity of
+    // k is static too.
+    auto half_step = [&](int k, auto u_c, auto la_c, auto lb_c, auto waitn_c) __attribute__((always_inline)) {
         constexpr int U = decltype(u_c)::value;
         constexpr int HP = U & 1;
+        constexpr bool LA = decltype(la_c)::value, LB = decltype(lb_c)::value;
         wait_loads_and_lds<decltype(waitn_c)::value>();
         __builtin_amdgcn_s_barrier();      // the stages of k are complete for everyone; nobody reads those of k-1 any more
         asm volatile("" ::: "memory");
@@ -313,19 +331,45 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         constexpr int nslot = (U + S - 1) % S;
         const int kn = k + S - 1;
         MOE_FENCE();
-        // group A: MFMAs of (k-1, sub-step 1); fetch (k, sub-step 0); activation-row loads
-        group(1, st, HP, 0, integral_constant<int, decltype(la_c)::value ? 1 : 0>{}, HP, nslot, kn, full);
-        // group B: MFMAs of (k, sub-step 0); fetch (k, sub-step 1); weight loads
-        group(0, st, HP, 1, integral_constant<int, decltype(lb_c)::value ? 2 : 0>{}, HP, nslot, kn, full);
+        constexpr int NF1 = NJ + 4;                         // fetches of group 1: B0, A0, B1 .. B(NJ-1), A1, A2, A3
+        constexpr int LA0 = NF1 + (NB == 2 ? 2 : 1), LAS = NB == 2 ? 4 : 2;     // MFMAs with an activation load behind them
+        using std::integral_constant;
+        static_for<NMF>([&](auto mc) __attribute__((always_inline)) {
+            constexpr int m = decltype(mc)::value;
+            mfma(integral_constant<int, 1>{}, integral_constant<int, HP ^ 1>{}, mc);
+            MOE_FENCE();
+            if (m < NF1) {
+                if (m == 1) fetch_a(HP, 0);
+                else if (m > NJ) fetch_a(HP, m - NJ);
+                else fetch_b(st, HP, m == 0 ? 0 : m - 1);
+                MOE_FENCE();
+            } else if (LA && m >= LA0 && (m - LA0) % LAS == 0 && (m - LA0) / LAS < 4) {
+                load_a(HP, (m - LA0) / LAS);
+                MOE_FENCE();
+            }
+        });
+        constexpr int LB0 = NB == 2 ? 8 : 6, LBS = NB == 2 ? 6 : 5;             // MFMAs with a weight load behind them
+        static_for<NMF>([&](auto mc) __attribute__((always_inline)) {
+            constexpr int m = decltype(mc)::value;
+            mfma(integral_constant<int, 0>{}, integral_constant<int, HP>{}, mc);
+            MOE_FENCE();
+            if (m < 4) {
+                fetch_a(HP, 4 + m);
+                MOE_FENCE();
+            } else if (LB && m >= LB0 && (m - LB0) % LBS == 0 && (m - LB0) / LBS < 2 * NB) {
+                load_b(nslot, kn, nslot & 1, (m - LB0) / LBS);
+                MOE_FENCE();
+            }
+        });
         if (HP) {                          // the next half-step reads the next activation stage
             const int d = (a_rd == kStagesA - 1) ? -(kStagesA - 1) * kStageA : kStageA;
             a_rd = (a_rd == kStagesA - 1) ? 0 : a_rd + 1;
-#pragma unroll
-            for (int x = 0; x < 4; ++x) a_frag[x >> 1][x & 1] += d;
+            a_frag[0] += d;
+            a_frag[1] += d;
         }
     };
 
-    auto main_loop = [&](auto full) __attribute__((always_inline)) {
+    auto main_loop = [&]() __attribute__((always_inline)) {
         using std::integral_constant;
         constexpr int kL = kLoadsPerStage;
         const std::true_type L{};
@@ -343,47 +387,54 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         }
         int k = 0;
         for (; k + S < KH; k += S) {
-            half_step(k, integral_constant<int, 0>{}, full, L, L, integral_constant<int, 2 * kL>{});
-            half_step(k + 1, integral_constant<int, 1>{}, full, L, L, integral_constant<int, 2 * kL>{});
-            half_step(k + 2, integral_constant<int, 2>{}, full, L, L, integral_constant<int, 2 * kL>{});
-            half_step(k + 3, integral_constant<int, 3>{}, full, L, L, integral_constant<int, 2 * kL>{});
+            half_step(k, integral_constant<int, 0>{}, L, L, integral_constant<int, 2 * kL>{});
+            half_step(k + 1, integral_constant<int, 1>{}, L, L, integral_constant<int, 2 * kL>{});
+            half_step(k + 2, integral_constant<int, 2>{}, L, L, integral_constant<int, 2 * kL>{});
+            half_step(k + 3, integral_constant<int, 3>{}, L, L, integral_constant<int, 2 * kL>{});
         }
         // last four half-steps: one more weight stage to load, then the rings drain
-        half_step(k, integral_constant<int, 0>{}, full, N, L, integral_constant<int, 2 * kL>{});
-        half_step(k + 1, integral_constant<int, 1>{}, full, N, N, integral_constant<int, kL + 2 * NB>{});
-        half_step(k + 2, integral_constant<int, 2>{}, full, N, N, integral_constant<int, 2 * NB>{});
-        half_step(k + 3, integral_constant<int, 3>{}, full, N, N, integral_constant<int, 0>{});
-        // the MFMAs of the last sub-step
+        half_step(k, integral_constant<int, 0>{}, N, L, integral_constant<int, 2 * kL>{});
+        half_step(k + 1, integral_constant<int, 1>{}, N, N, integral_constant<int, kL + 2 * NB>{});
+        half_step(k + 2, integral_constant<int, 2>{}, N, N, integral_constant<int, 2 * NB>{});
+        half_step(k + 3, integral_constant<int, 3>{}, N, N, integral_constant<int, 0>{});
+        // row tiles 4..7 of the last half-step (weight fragment set 1: KH is even)
         __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
-#pragma unroll
-        for (int j = 0; j < NMF; ++j) mfma(1, j, full);
+        static_for<NMF>([&](auto mc) __attribute__((always_inline)) { mfma(integral_constant<int, 1>{}, integral_constant<int, 1>{}, mc); });
+        mfma_drain();
     };
     MOE_TL(2);
-    // a row tile whose last rows are missing skips the MFMA tiles that hold no valid row
-    if (n_ms == 4) main_loop(std::true_type{});
-    else main_loop(std::false_type{});
+    // A row tile whose last rows are missing runs the same loop on repeated rows: skipping the MFMA
+    // tiles without a valid row takes a branch per MFMA (a wavefront issues about one instruction in
+    // four clocks, and the branches cost more than the 16 clocks of the MFMA they skip).
+    main_loop();
     MOE_TL(3);
 
     // ---- epilogue ---------------------------------------------------------------------
-    // accumulator register r of lane l in MFMA tile (ms, ns) is the element at
-    // row ms*32 + (r/4)*8 + (l/32)*4 + r%4, column l%32 of that 32 x 32 tile
-    const int col_l = lane & 31;
-    const int a_row_base = wm * 128;
+    // accumulator register r of lane l in MFMA tile (i, j) is the element at row i*16 + (l/16)*4 + r,
+    // column l%16 of that 16 x 16 tile
+    const int col_l = lane & 15;
+    const int a_row_base = wm * 128 + (lane >> 4) * 4;
     const bool full_rows = rows_here == BM;
     if (MODE == 0) {
         __bf16* h = (__bf16*)p.out + (int64_t)row0 * p.ldo + nt * 128 + wn * 64 + col_l;
         auto store_rows = [&](auto full) __attribute__((always_inline)) {
+            static_for<8>([&](auto ic) __attribute__((always_inline)) {
+                constexpr int i = decltype(ic)::value;
+                float v[NJ][4];
+                static_for<NJ * 4>([&](auto c) __attribute__((always_inline)) {
+                    constexpr int q = decltype(c)::value;
+                    v[q >> 2][q & 3] = acc_read<i * NJ * 4 + q>();
+                });
 #pragma unroll
-            for (int ms = 0; ms < 4; ++ms)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = a_row_base + ms * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                for (int r = 0; r < 4; ++r) {
+                    const int row = a_row_base + i * 16 + r;
                     if (decltype(full)::value || row < rows_here) {
 #pragma unroll
-                        for (int ns = 0; ns < 2; ++ns)
-                            h[(int64_t)row * p.ldo + ns * 32] = (__bf16)silu_mul(acc[ms][ns][r], acc[ms][ns + 2][r]);
+                        for (int j = 0; j < 4; ++j)
+                            h[(int64_t)row * p.ldo + j * 16] = (__bf16)silu_mul(v[j][r], v[j + 4][r]);
                     }
                 }
+            });
         };
         if (full_rows) store_rows(std::true_type{});
         else store_rows(std::false_type{});
@@ -394,27 +445,30 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         __syncthreads();                       // every wavefront has left the main loop
         sw[tid] = (p.row_w && tid < rows_here) ? p.row_w[row0 + tid] : 1.0f;
         __syncthreads();
-        const int d0 = nt * (128 * NB) + wn * (32 * NS);   // n_cols is a multiple of 128: with NB = 2 a wavefront's columns are all valid or all not
+        const int d0 = nt * (128 * NB) + wn * (16 * NJ);   // n_cols is a multiple of 128: with NB = 2 a wavefront's columns are all valid or all not
         if (d0 < p.n_cols) {
             float* o = (float*)p.out + (int64_t)row0 * p.ldo + d0 + col_l;
             auto store_rows = [&](auto full) __attribute__((always_inline)) {
+                static_for<8>([&](auto ic) __attribute__((always_inline)) {
+                    constexpr int i = decltype(ic)::value;
+                    float v[NJ][4];
+                    static_for<NJ * 4>([&](auto c) __attribute__((always_inline)) {
+                        constexpr int q = decltype(c)::value;
+                        v[q >> 2][q & 3] = acc_read<i * NJ * 4 + q>();
+                    });
+                    const int rowq = a_row_base + i * 16;      // 4 consecutive rows
+                    const float4 wq = *(const float4*)(sw + rowq);
+                    const float w4[4] = {wq.x, wq.y, wq.z, wq.w};
 #pragma unroll
-                for (int ms = 0; ms < 4; ++ms)
+                    for (int r = 0; r < 4; ++r) {
+                        const int row = rowq + r;
+                        if (decltype(full)::value || row < rows_here) {
 #pragma unroll
-                    for (int rq = 0; rq < 4; ++rq) {
-                        const int rowq = a_row_base + ms * 32 + rq * 8 + (lane >> 5) * 4;      // 4 consecutive rows
-                        const float4 wq = *(const float4*)(sw + rowq);
-                        const float w4[4] = {wq.x, wq.y, wq.z, wq.w};
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int row = rowq + i;
-                            if (decltype(full)::value || row < rows_here) {
-#pragma unroll
-                                for (int ns = 0; ns < NS; ++ns)
-                                    o[(int64_t)row * p.ldo + ns * 32] = acc[ms][ns][rq * 4 + i] * w4[i];
-                            }
+                            for (int j = 0; j < NJ; ++j)
+                                o[(int64_t)row * p.ldo + j * 16] = v[j][r] * w4[r];
                         }
                     }
+                });
             };
             if (full_rows) store_rows(std::true_type{});
             else store_rows(std::false_type{});
