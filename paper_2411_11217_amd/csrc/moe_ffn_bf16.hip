@@ -123,6 +123,19 @@ __device__ __forceinline__ void mfma_16x16x32(const i32x4& a, const i32x4& b) { 
     asm volatile("v_mfma_f32_16x16x32_bf16 a[%2:%3], %0, %1, a[%2:%3]" ::"v"(a), "v"(b), "n"(R), "n"(R + 3));
 #endif
 }
+// The same MFMA with one global -> LDS load of 16 bytes per lane behind it: LDS address
+// lds_base + LDS_IMM + lane * 16 (through M0, written before the MFMA so that the MFMA fills the
+// wait state the load needs after it), global address base + offset[lane].  One statement, so nothing
+// can come between the write of M0 and the load; the scalar base + 32-bit lane offset form of the load
+// needs no 64-bit vector addition (the builtin's flat-pointer form costs one per load).
+template <int R, int LDS_IMM>
+__device__ __forceinline__ void mfma_16x16x32_then_load(const i32x4& a, const i32x4& b, const char* base, uint32_t offset, uint32_t lds_base) {
+#ifdef __HIP_DEVICE_COMPILE__
+    asm volatile("s_add_i32 m0, %4, %5\n\tv_mfma_f32_16x16x32_bf16 a[%6:%7], %0, %1, a[%6:%7]\n\tglobal_load_lds_dwordx4 %2, %3"
+                 ::"v"(a), "v"(b), "v"(offset), "s"(base), "s"(lds_base), "n"(LDS_IMM), "n"(R), "n"(R + 3)
+                 : "memory", "m0");
+#endif
+}
 template <int R>
 __device__ __forceinline__ void acc_zero() {
 #ifdef __HIP_DEVICE_COMPILE__
@@ -247,13 +260,32 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     // k-step two ahead, and the weight stage of half-step h + 3 (instructions 4, 5: half-tile 0; 6, 7:
     // half-tile 1) into weight slot `slot`.  After the last instruction of a kind the sources move on.
     const int KH = 2 * p.KT;
-    auto load_a = [&](int part, int i) __attribute__((always_inline)) {
-        const int ia = part * 4 + i;
-        __builtin_amdgcn_global_load_lds((gptr_t)(a_ptr + a_off[ia]), (lptr_t)(smem + a_wr + (ia * kWaves + wave) * 1024), 16, 0, 0);
+    const uint32_t lds_wave = (uint32_t)(uintptr_t)(lptr_t)smem + wave * 1024;      // LDS address of this wavefront's 1 KiB inside a 4 KiB load group
+    uint32_t a_wr_w = lds_wave + kRingA;                       // the same inside the activation stage being filled
+    const uint32_t a_wr_last = lds_wave + kRingA + (kStagesA - 1) * kStageA;
+    uint32_t b_voff[2][2];                                      // [odd half-step][first or second 4 KiB of the half-tile]
+#pragma unroll
+    for (int o = 0; o < 2; ++o)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) b_voff[o][h] = o * kHalfTile + h * (kWaves * 1024) + b_off;
+    auto advance_a = [&](int ia) __attribute__((always_inline)) {
         if (ia == 7) {
             a_ptr += kARowB;
             a_wr = (a_wr == kRingA + (kStagesA - 1) * kStageA) ? kRingA : a_wr + kStageA;
+            a_wr_w = (a_wr_w == a_wr_last) ? lds_wave + kRingA : a_wr_w + kStageA;
         }
+    };
+    auto advance_b = [&](int kn, int odd, int i) __attribute__((always_inline)) {
+        if (i == 2 * NB - 1 && odd && kn + 1 < KH) {
+            walk_next(w0);
+            if (NB == 2) walk_next(w1);
+        }
+    };
+    // the loads of the prologue (no MFMA to pair them with)
+    auto load_a = [&](int part, int i) __attribute__((always_inline)) {
+        const int ia = part * 4 + i;
+        __builtin_amdgcn_global_load_lds((gptr_t)(a_ptr + a_off[ia]), (lptr_t)(smem + a_wr + (ia * kWaves + wave) * 1024), 16, 0, 0);
+        advance_a(ia);
     };
     auto load_b = [&](int slot, int kn, int odd, int i) __attribute__((always_inline)) {     // odd = kn & 1, known at compile time by the callers
         char* st = smem + slot * kStageB;
@@ -261,10 +293,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         const int part = (i & 1) * (kWaves * 1024);                       // first or second 4 KiB of the half-tile
         const char* b = w.tile + odd * kHalfTile + part;
         __builtin_amdgcn_global_load_lds((gptr_t)(b + b_off), (lptr_t)(st + (i >= 2 ? kHalfTile : 0) + part + wave * 1024), 16, 0, 0);
-        if (i == 2 * NB - 1 && odd && kn + 1 < KH) {
-            walk_next(w0);
-            if (NB == 2) walk_next(w1);
-        }
+        advance_b(kn, odd, i);
     };
 
     // accumulator tile (i, j), rows wm*128 + i*16, columns by B fragment j: registers a[(i*NJ + j)*4 ..+3]
@@ -308,6 +337,22 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         constexpr int i = half * 4 + m / NJ, j = m % NJ;
         mfma_16x16x32<(i * NJ + j) * 4>(half ? AY[m / NJ] : AX[m / NJ], BF[set][j]);
     };
+    // MFMA m of the row tiles 4..7 (set: weight fragments) followed by activation load instruction IA
+    auto mfma_load_a = [&](auto set_c, auto m_c, auto ia_c) __attribute__((always_inline)) {
+        constexpr int set = decltype(set_c)::value, m = decltype(m_c)::value, IA = decltype(ia_c)::value;
+        constexpr int i = 4 + m / NJ, j = m % NJ;
+        mfma_16x16x32_then_load<(i * NJ + j) * 4, IA * kWaves * 1024>(AY[m / NJ], BF[set][j], a_ptr, a_off[IA], a_wr_w);
+        advance_a(IA);
+    };
+    // MFMA m of the row tiles 0..3 followed by weight load instruction I of half-step kn into slot SLOT
+    auto mfma_load_b = [&](auto set_c, auto m_c, auto slot_c, auto i_c, int kn) __attribute__((always_inline)) {
+        constexpr int set = decltype(set_c)::value, m = decltype(m_c)::value, SLOT = decltype(slot_c)::value, I = decltype(i_c)::value;
+        constexpr int i = m / NJ, j = m % NJ;
+        constexpr int odd = SLOT & 1;               // S is even: the parity of the half-step is that of its slot
+        mfma_16x16x32_then_load<(i * NJ + j) * 4, SLOT * kStageB + (I >= 2 ? kHalfTile : 0) + (I & 1) * (kWaves * 1024)>(
+            AX[m / NJ], BF[set][j], (I < 2 ? w0 : w1).tile, b_voff[odd][I & 1], lds_wave);
+        advance_b(kn, odd, I);
+    };
 
     // One half-step on weight-ring slot U (a compile-time constant: every weight address in LDS is an
     // immediate; the activation stage moves through per-lane offsets).  Two groups of NMF MFMAs with
@@ -336,28 +381,26 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         using std::integral_constant;
         static_for<NMF>([&](auto mc) __attribute__((always_inline)) {
             constexpr int m = decltype(mc)::value;
-            mfma(integral_constant<int, 1>{}, integral_constant<int, HP ^ 1>{}, mc);
+            constexpr bool ld = LA && m >= LA0 && (m - LA0) % LAS == 0 && (m - LA0) / LAS < 4;
+            if constexpr (ld) mfma_load_a(integral_constant<int, HP ^ 1>{}, mc, integral_constant<int, HP * 4 + (m - LA0) / LAS>{});
+            else mfma(integral_constant<int, 1>{}, integral_constant<int, HP ^ 1>{}, mc);
             MOE_FENCE();
             if (m < NF1) {
                 if (m == 1) fetch_a(HP, 0);
                 else if (m > NJ) fetch_a(HP, m - NJ);
                 else fetch_b(st, HP, m == 0 ? 0 : m - 1);
                 MOE_FENCE();
-            } else if (LA && m >= LA0 && (m - LA0) % LAS == 0 && (m - LA0) / LAS < 4) {
-                load_a(HP, (m - LA0) / LAS);
-                MOE_FENCE();
             }
         });
         constexpr int LB0 = NB == 2 ? 8 : 6, LBS = NB == 2 ? 6 : 5;             // MFMAs with a weight load behind them
         static_for<NMF>([&](auto mc) __attribute__((always_inline)) {
             constexpr int m = decltype(mc)::value;
-            mfma(integral_constant<int, 0>{}, integral_constant<int, HP>{}, mc);
+            constexpr bool ld = LB && m >= LB0 && (m - LB0) % LBS == 0 && (m - LB0) / LBS < 2 * NB;
+            if constexpr (ld) mfma_load_b(integral_constant<int, HP>{}, mc, integral_constant<int, nslot>{}, integral_constant<int, ld ? (m - LB0) / LBS : 0>{}, kn);
+            else mfma(integral_constant<int, 0>{}, integral_constant<int, HP>{}, mc);
             MOE_FENCE();
             if (m < 4) {
                 fetch_a(HP, 4 + m);
-                MOE_FENCE();
-            } else if (LB && m >= LB0 && (m - LB0) % LBS == 0 && (m - LB0) / LBS < 2 * NB) {
-                load_b(nslot, kn, nslot & 1, (m - LB0) / LBS);
                 MOE_FENCE();
             }
         });
