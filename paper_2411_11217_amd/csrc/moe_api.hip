@@ -14,12 +14,11 @@ void set_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
 
 // ---- options ----------------------------------------------------------------
 static int g_opts[OPT_COUNT] = {
-    /*OPT_XCD_REMAP*/ 1,     // 1: tiles are dealt to the 8 XCDs in contiguous chunks
+    /*OPT_XCD_REMAP*/ 1,     // 1: the column tiles of the expert GEMMs are dealt round robin to the 8 XCDs
     /*OPT_PROFILE*/ 0,       // 1: moe_layer records stage events (see moe_profile_read)
-    /*OPT_TILE_ORDER*/ 1,    // 0: partial row tiles after all full ones; 1: next to the full row tiles of their column tile
     /*OPT_DOWN_COLS*/ 0,     // column tiles of the bf16 down GEMM: 0 = by grid size, 1 = 128 wide, 2 = 256 wide
 };
-static const char* g_opt_names[OPT_COUNT] = {"xcd_remap", "profile", "tile_order", "down_cols"};
+static const char* g_opt_names[OPT_COUNT] = {"xcd_remap", "profile", "down_cols"};
 int get_opt(int id) { return g_opts[id]; }
 
 int validate_shape(const moe_shape* s) {

@@ -588,7 +588,6 @@ int launch_linear_bf16(const LinearArgs& a, hipStream_t st) {
     p.row_w = nullptr;
     p.status = a.status;
     p.xcd_remap = get_opt(OPT_XCD_REMAP);
-    p.tile_order = get_opt(OPT_TILE_ORDER);
     const int wide_tiles = (p.n_page_tiles + 1) / 2;
     if ((int64_t)(a.T / BM + 1) * wide_tiles < 2 * kComputeUnits) {       // too few 256-wide tiles to fill the chip
         p.NT = p.n_page_tiles;

@@ -30,7 +30,6 @@ struct GemmParams {
     const float* row_w;
     int32_t* status;
     int32_t xcd_remap;
-    int32_t tile_order;
 };
 
 struct TileCoord {
@@ -38,18 +37,16 @@ struct TileCoord {
     bool valid;
 };
 
-// Tile order.  Numbers run over the row tiles of one column tile first (they share the
-// weight tiles), then over the column tiles, then over the experts, and with xcd_remap
-// they are dealt to the 8 XCDs (block b runs on XCD b % 8, each with its own L2) in
-// contiguous chunks, so that the blocks an XCD runs at the same time are a few row tiles
-// times a few column tiles of one expert.  The at most one PARTIAL row tile at the end
-// of an expert's segment is cheaper than a full one (MFMA tiles without valid rows are
-// skipped).  tile_order 1 (default) numbers it right after the full row tiles of its
-// column tile, so that it finds the weight tiles in L2; tile_order 0 numbers all partial
-// tiles after all full ones (longest first), which fills the end of the launch better but
-// was measured to read every weight tile from memory a second time (+26 % L2 misses,
-// +5 % time on the Mixtral-8x7B-shaped workload).  The tile counts come from offsets[],
-// so the grid is only an upper bound and surplus blocks leave at once.
+// Tile order.  The row tiles of one column tile of one expert form a GROUP (they share
+// the weight tiles); groups are numbered expert by expert, column tile by column tile.
+// With xcd_remap the groups are dealt round robin to the 8 XCDs (block b runs on XCD
+// b % 8, each with its own L2): XCD x works through the groups x, x + 8, x + 16, ...
+// row tile by row tile, so the blocks an XCD runs at the same time are the row tiles of a
+// few column tiles of one expert, and every XCD gets the same mix of experts, hence of
+// full and partial row tiles (contiguous chunks of the numbering gave one XCD 22 % more
+// full tiles than another on the Mixtral-8x7B-shaped workload).  Without it block b takes
+// tile b of the plain numbering.  The tile counts come from offsets[], so the grid is only
+// an upper bound and surplus blocks leave at once.
 //
 // Every wavefront does the search on its own, one expert per lane (at most 64
 // experts): one load of the segment bounds, prefix sums of the tile counts over
@@ -75,46 +72,28 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
         seg0 = p.offsets[e_l];
         cnt = p.offsets[e_l + 1] - seg0;
     }
-    // tile_order 0: partial row tiles form a class of their own; 1: one class, the partial
-    // row tile of an expert is numbered right after its full row tiles
-    const int full_l = p.tile_order ? (cnt + BM - 1) / BM : cnt / BM;   // row tiles of my expert in the first class
-    const int part_l = p.tile_order ? 0 : (cnt % BM) != 0;              // 0 or 1 partial row tile
-    const int full_incl = lane_prefix_sum(full_l, lane);
-    const int part_incl = lane_prefix_sum(part_l, lane);
-    const int total_full = __builtin_amdgcn_readlane(full_incl, 63) * p.NT;
-    const int total_part = __builtin_amdgcn_readlane(part_incl, 63) * p.NT;
-    // position in the launch order -> (class, number inside the class)
-    int L = blockIdx.x;
-    bool partial;
-    if (p.xcd_remap) {
-        const int chunk_f = (total_full + 7) >> 3, chunk_p = (total_part + 7) >> 3;
-        const int xcd = blockIdx.x & 7;
-        int idx = blockIdx.x >> 3;
-        partial = idx >= chunk_f;
-        if (partial) {
-            idx -= chunk_f;
-            if (idx >= chunk_p) return t;
-            L = xcd * chunk_p + idx;
-        } else {
-            L = xcd * chunk_f + idx;
-        }
-    } else {
-        partial = L >= total_full;
-        if (partial) L -= total_full;
-    }
-    if (L >= (partial ? total_part : total_full)) return t;
-    const int incl = partial ? part_incl : full_incl;
-    const int mine = partial ? part_l : full_l;
-    const unsigned long long holds = __ballot(L < incl * p.NT);      // lanes of this and later experts
+    const int stride = p.xcd_remap ? 8 : 1;
+    const int x = p.xcd_remap ? (int)(blockIdx.x & 7) : 0;           // my groups: x, x + stride, ...
+    const int idx = p.xcd_remap ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;    // my position among their row tiles
+    // groups of mine below group number n: ceil((n - x) / stride) for n >= 0 (0 <= x < stride)
+    const int g_lo = lane * p.NT, g_hi = g_lo + p.NT;              // group numbers of my lane's expert
+    const int c_lo = (g_lo - x + stride - 1) / stride, c_hi = (g_hi - x + stride - 1) / stride;
+    const int mtiles_l = (cnt + BM - 1) / BM;                        // row tiles of my lane's expert
+    const int tiles_l = (c_hi - c_lo) * mtiles_l;
+    const int incl = lane_prefix_sum(tiles_l, lane);
+    if (idx >= __builtin_amdgcn_readlane(incl, 63)) return t;
+    const unsigned long long holds = __ballot(idx < incl);           // lanes of this and later experts
     const int src = __builtin_amdgcn_readfirstlane(__ffsll((long long)holds) - 1);
-    const int mtiles = __builtin_amdgcn_readfirstlane(__shfl(mine, src, 64));
-    const int before = __builtin_amdgcn_readfirstlane(__shfl(incl - mine, src, 64));
+    const int mtiles = __builtin_amdgcn_readfirstlane(__shfl(mtiles_l, src, 64));
+    const int before = __builtin_amdgcn_readfirstlane(__shfl(incl - tiles_l, src, 64));
+    const int first = __builtin_amdgcn_readfirstlane(__shfl(c_lo, src, 64));       // my groups before this expert
     const int seg = __builtin_amdgcn_readfirstlane(__shfl(seg0, src, 64));
     const int rows = __builtin_amdgcn_readfirstlane(__shfl(cnt, src, 64));
-    L -= before * p.NT;
+    const int rem = idx - before;
+    const int j = rem / mtiles;                                        // my j-th group inside this expert
     t.e = p.e_begin + src;
-    t.nt = L / mtiles;
-    t.mt = partial ? rows / BM : L - t.nt * mtiles;
+    t.nt = x + (first + j) * stride - src * p.NT;
+    t.mt = rem - j * mtiles;
     t.row0 = seg + t.mt * BM;
     t.rows_here = min(BM, rows - t.mt * BM);
     t.valid = t.rows_here > 0;
@@ -134,10 +113,11 @@ __device__ __forceinline__ const char* tile_address(const GemmParams& p, const i
     return p.pool + (int64_t)slot * p.page_bytes + (int64_t)within * p.tile_bytes;
 }
 
-// grid size that covers every tile for any routing result
+// grid size that covers every tile for any routing result: an XCD gets at most ceil(NT / 8) of an
+// expert's NT groups, each with that expert's row tiles
 inline int gemm_grid(int NT, int R, int BM, int n_experts) {
     const int m_tiles_max = R / BM + n_experts;   // >= sum over experts of ceil(rows / BM)
-    return ((NT * m_tiles_max + 7) / 8 + 2) * 8;   // each of the two tile classes is rounded up to a multiple of 8
+    return 8 * ((NT + 7) / 8) * m_tiles_max;
 }
 
 inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const FfnArgs& a) {
@@ -154,7 +134,6 @@ inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const 
     p.table_row_mod = a.table_row_mod;
     p.status = a.status;
     p.xcd_remap = get_opt(OPT_XCD_REMAP);
-    p.tile_order = get_opt(OPT_TILE_ORDER);
 }
 
 // parameters of the gate/up launch (K = H, output h[R][F]) and of the down launch

@@ -115,10 +115,11 @@ def test_reduced_cases_stagewise_and_layer(name, down_cols):
         M.set_option("down_cols", 0)
 
 
-@pytest.mark.parametrize("option,default", [("xcd_remap", 1), ("tile_order", 1)])
-def test_tile_numbering_options_give_identical_bits(option, default):
+@pytest.mark.parametrize("name", ["bf16_top2_of_4", "bf16_two_experts_ragged", "f32_top2_of_5"])
+@pytest.mark.parametrize("option,default", [("xcd_remap", 1)])
+def test_tile_numbering_options_give_identical_bits(option, default, name):
     # which block computes which tile does not change any arithmetic
-    case = Case(MED["bf16_top2_of_4"])
+    case = Case(MED[name])
     y1, _ = M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev)
     M.set_option(option, 1 - default)
     try:
