@@ -304,11 +304,6 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     // of the four a half-step has.  Weights (64-byte rows, one half-step per stage): chunk lane/16;
     // activations (128-byte rows, two half-steps per stage): chunk 4*hp + lane/16 in half-step parity hp.
     const int b_frag0 = (lane & 15) * kRowB + ((((lane >> 4) ^ ((lane >> 2) & 3)) & 3) << 4);
-    int a_frag[2];                    // includes the activation stage being read: moves on after every odd half-step
-#pragma unroll
-    for (int hp = 0; hp < 2; ++hp)
-        a_frag[hp] = kRingA + wm * 128 * kARowB + (lane & 15) * kARowB + (((4 * hp + (lane >> 4)) ^ ((lane >> 1) & 7)) << 4);
-    int a_rd = 0;                     // activation stage being read
     // B fragment j: MODE 0: gate rows wn*64 + (j%4)*16 of tile 0 (j < 4), the same up rows of tile 1 (j >= 4);
     //               MODE 1: rows wn*(16*NJ) + j*16 of the 128*NB rows of the block's tiles
     int b_base[NJ];
@@ -316,105 +311,152 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     for (int j = 0; j < NJ; ++j)
         b_base[j] = ((MODE == 0) ? (j >> 2) * 128 + wn * 64 + (j & 3) * 16 : wn * (16 * NJ) + j * 16) * kRowB;
 
-    // operand registers: activation fragments of row tiles 0..3 (AX) and 4..7 (AY), weight fragments of
-    // two half-steps (the MFMAs of row tiles 4..7 run one half-step behind, see below)
+    // operand registers: two sets of four activation fragments, two sets of weight fragments
     i32x4 AX[4], AY[4], BF[2][NJ];
 #pragma unroll
     for (int i = 0; i < 4; ++i) AX[i] = AY[i] = i32x4{0, 0, 0, 0};
 #pragma unroll
     for (int j = 0; j < NJ; ++j) BF[0][j] = BF[1][j] = i32x4{0, 0, 0, 0};   // the first rotated MFMA group adds 0 * 0
 
-    auto fetch_a = [&](int hp, int i) __attribute__((always_inline)) {      // row tile i = 0..7 of the activation stage being read
-        const i32x4 v = *(const i32x4*)(smem + a_frag[hp] + i * 16 * kARowB);
-        if (i < 4) AX[i] = v;
-        else AY[i - 4] = v;
-    };
     auto fetch_b = [&](const char* st, int set, int j) __attribute__((always_inline)) {     // st: weight stage
         BF[set][j] = *(const i32x4*)(st + b_base[j] + b_frag0);
     };
-    auto mfma = [&](auto half_c, auto set_c, auto m_c) __attribute__((always_inline)) {    // m = 0..NMF-1: row tile half*4 + m / NJ, fragment m % NJ
-        constexpr int half = decltype(half_c)::value, set = decltype(set_c)::value, m = decltype(m_c)::value;
-        constexpr int i = half * 4 + m / NJ, j = m % NJ;
-        mfma_16x16x32<(i * NJ + j) * 4>(half ? AY[m / NJ] : AX[m / NJ], BF[set][j]);
+    // accumulator tile (I, J) += a * b, alone or with a load behind it
+    auto mfma = [&](auto i_c, auto j_c, const i32x4& a, const i32x4& b) __attribute__((always_inline)) {
+        mfma_16x16x32<(decltype(i_c)::value * NJ + decltype(j_c)::value) * 4>(a, b);
     };
-    // MFMA m of the row tiles 4..7 (set: weight fragments) followed by activation load instruction IA
-    auto mfma_load_a = [&](auto set_c, auto m_c, auto ia_c) __attribute__((always_inline)) {
-        constexpr int set = decltype(set_c)::value, m = decltype(m_c)::value, IA = decltype(ia_c)::value;
-        constexpr int i = 4 + m / NJ, j = m % NJ;
-        mfma_16x16x32_then_load<(i * NJ + j) * 4, IA * kWaves * 1024>(AY[m / NJ], BF[set][j], a_ptr, a_off[IA], a_wr_w);
+    auto mfma_load_a = [&](auto i_c, auto j_c, const i32x4& a, const i32x4& b, auto ia_c) __attribute__((always_inline)) {   // + activation load instruction IA
+        constexpr int IA = decltype(ia_c)::value;
+        mfma_16x16x32_then_load<(decltype(i_c)::value * NJ + decltype(j_c)::value) * 4, IA * kWaves * 1024>(a, b, a_ptr, a_off[IA], a_wr_w);
         advance_a(IA);
     };
-    // MFMA m of the row tiles 0..3 followed by weight load instruction I of half-step kn into slot SLOT
-    auto mfma_load_b = [&](auto set_c, auto m_c, auto slot_c, auto i_c, int kn) __attribute__((always_inline)) {
-        constexpr int set = decltype(set_c)::value, m = decltype(m_c)::value, SLOT = decltype(slot_c)::value, I = decltype(i_c)::value;
-        constexpr int i = m / NJ, j = m % NJ;
+    auto mfma_load_b = [&](auto i_c, auto j_c, const i32x4& a, const i32x4& b, auto slot_c, auto l_c, int kn) __attribute__((always_inline)) {   // + weight load instruction L of half-step kn into slot SLOT
+        constexpr int SLOT = decltype(slot_c)::value, I = decltype(l_c)::value;
         constexpr int odd = SLOT & 1;               // S is even: the parity of the half-step is that of its slot
-        mfma_16x16x32_then_load<(i * NJ + j) * 4, SLOT * kStageB + (I >= 2 ? kHalfTile : 0) + (I & 1) * (kWaves * 1024)>(
-            AX[m / NJ], BF[set][j], (I < 2 ? w0 : w1).tile, b_voff[odd][I & 1], lds_wave);
+        mfma_16x16x32_then_load<(decltype(i_c)::value * NJ + decltype(j_c)::value) * 4, SLOT * kStageB + (I >= 2 ? kHalfTile : 0) + (I & 1) * (kWaves * 1024)>(
+            a, b, (I < 2 ? w0 : w1).tile, b_voff[odd][I & 1], lds_wave);
         advance_b(kn, odd, I);
     };
 
-    // One half-step on weight-ring slot U (a compile-time constant: every weight address in LDS is an
-    // immediate; the activation stage moves through per-lane offsets).  Two groups of NMF MFMAs with
-    // the other instructions spread between them, at most one behind an MFMA:
+    // The main loop for a tile of 256 rows (HALF = false) or of at most 128 rows (HALF = true).
+    //
+    // 256 rows: wavefront (wm, wn) owns rows wm*128 .. +127: row tiles 0..3 through the fragment set AX,
+    // 4..7 through AY.  A half-step on weight-ring slot U (a compile-time constant: every weight address
+    // in LDS is an immediate; the activation stage moves through per-lane offsets) is two groups of
+    // MFMAs with the other instructions spread between them, at most one behind an MFMA:
     //   group 1: row tiles 4..7 of half-step k-1 (operands fetched during k-1); fetches the weight
     //            fragments of k and the activation fragments of row tiles 0..3; issues the activation loads;
     //   group 2: row tiles 0..3 of half-step k; fetches the activation fragments of row tiles 4..7;
     //            issues the weight loads.
+    // At most 128 rows: wavefront (wm, wn) owns rows wm*64 .. +63, four row tiles; the two fragment sets
+    // alternate between half-steps, and the groups split the columns instead:
+    //   group 1: the second half of the column fragments of half-step k-1; fetches all fragments of k;
+    //            issues the activation loads (even half-steps only: rows 128..255 are not loaded at all);
+    //   group 2: the first half of the column fragments of half-step k; issues the weight loads.
+    // Such a tile costs about half the MFMAs and three quarters of the loads of a full one.
     // LA / LB: issue the activation / weight loads of this half-step.  WAITN: my loads that may still
     // be in flight when the stages of half-step k must be complete (those issued during the two
     // half-steps before).  Weight fragment set U & 1 belongs to half-step k: S is even, so the parity of
     // k is static too.
-    auto half_step = [&](int k, auto u_c, auto la_c, auto lb_c, auto waitn_c) __attribute__((always_inline)) {
-        constexpr int U = decltype(u_c)::value;
-        constexpr int HP = U & 1;
-        constexpr bool LA = decltype(la_c)::value, LB = decltype(lb_c)::value;
-        wait_loads_and_lds<decltype(waitn_c)::value>();
-        __builtin_amdgcn_s_barrier();      // the stages of k are complete for everyone; nobody reads those of k-1 any more
-        asm volatile("" ::: "memory");
-        const char* st = smem + U * kStageB;
-        constexpr int nslot = (U + S - 1) % S;
-        const int kn = k + S - 1;
-        MOE_FENCE();
-        constexpr int NF1 = NJ + 4;                         // fetches of group 1: B0, A0, B1 .. B(NJ-1), A1, A2, A3
-        constexpr int LA0 = NF1 + (NB == 2 ? 2 : 1), LAS = NB == 2 ? 4 : 2;     // MFMAs with an activation load behind them
+    auto main_loop = [&](auto half_tile_c) __attribute__((always_inline)) {
         using std::integral_constant;
-        static_for<NMF>([&](auto mc) __attribute__((always_inline)) {
-            constexpr int m = decltype(mc)::value;
-            constexpr bool ld = LA && m >= LA0 && (m - LA0) % LAS == 0 && (m - LA0) / LAS < 4;
-            if constexpr (ld) mfma_load_a(integral_constant<int, HP ^ 1>{}, mc, integral_constant<int, HP * 4 + (m - LA0) / LAS>{});
-            else mfma(integral_constant<int, 1>{}, integral_constant<int, HP ^ 1>{}, mc);
-            MOE_FENCE();
-            if (m < NF1) {
-                if (m == 1) fetch_a(HP, 0);
-                else if (m > NJ) fetch_a(HP, m - NJ);
-                else fetch_b(st, HP, m == 0 ? 0 : m - 1);
-                MOE_FENCE();
-            }
-        });
-        constexpr int LB0 = NB == 2 ? 8 : 6, LBS = NB == 2 ? 6 : 5;             // MFMAs with a weight load behind them
-        static_for<NMF>([&](auto mc) __attribute__((always_inline)) {
-            constexpr int m = decltype(mc)::value;
-            constexpr bool ld = LB && m >= LB0 && (m - LB0) % LBS == 0 && (m - LB0) / LBS < 2 * NB;
-            if constexpr (ld) mfma_load_b(integral_constant<int, HP>{}, mc, integral_constant<int, nslot>{}, integral_constant<int, ld ? (m - LB0) / LBS : 0>{}, kn);
-            else mfma(integral_constant<int, 0>{}, integral_constant<int, HP>{}, mc);
-            MOE_FENCE();
-            if (m < 4) {
-                fetch_a(HP, 4 + m);
-                MOE_FENCE();
-            }
-        });
-        if (HP) {                          // the next half-step reads the next activation stage
-            const int d = (a_rd == kStagesA - 1) ? -(kStagesA - 1) * kStageA : kStageA;
-            a_rd = (a_rd == kStagesA - 1) ? 0 : a_rd + 1;
-            a_frag[0] += d;
-            a_frag[1] += d;
-        }
-    };
+        constexpr bool HALF = decltype(half_tile_c)::value;
+        constexpr int WROWS = HALF ? 64 : 128;          // rows of a wavefront
+        int a_frag[2];                    // includes the activation stage being read: moves on after every odd half-step
+#pragma unroll
+        for (int hp = 0; hp < 2; ++hp)
+            a_frag[hp] = kRingA + wm * WROWS * kARowB + (lane & 15) * kARowB + (((4 * hp + (lane >> 4)) ^ ((lane >> 1) & 7)) << 4);
+        int a_rd = 0;                     // activation stage being read
+        auto fetch_a = [&](int hp, int i, i32x4& dst) __attribute__((always_inline)) {      // row tile i of this wavefront in the activation stage being read
+            dst = *(const i32x4*)(smem + a_frag[hp] + i * 16 * kARowB);
+        };
 
-    auto main_loop = [&]() __attribute__((always_inline)) {
-        using std::integral_constant;
-        constexpr int kL = kLoadsPerStage;
+        auto half_step = [&](int k, auto u_c, auto la_c, auto lb_c, auto waitn_c) __attribute__((always_inline)) {
+            constexpr int U = decltype(u_c)::value;
+            constexpr int HP = U & 1;
+            constexpr bool LA = decltype(la_c)::value, LB = decltype(lb_c)::value;
+            wait_loads_and_lds<decltype(waitn_c)::value>();
+            __builtin_amdgcn_s_barrier();      // the stages of k are complete for everyone; nobody reads those of k-1 any more
+            asm volatile("" ::: "memory");
+            const char* st = smem + U * kStageB;
+            constexpr int nslot = (U + S - 1) % S;
+            const int kn = k + S - 1;
+            MOE_FENCE();
+            if constexpr (!HALF) {
+                constexpr int NF1 = NJ + 4;                         // fetches of group 1: B0, A0, B1 .. B(NJ-1), A1, A2, A3
+                constexpr int LA0 = NF1 + (NB == 2 ? 2 : 1), LAS = NB == 2 ? 4 : 2;     // MFMAs with an activation load behind them
+                static_for<NMF>([&](auto mc) __attribute__((always_inline)) {
+                    constexpr int m = decltype(mc)::value;
+                    constexpr int r = m / NJ, j = m % NJ;
+                    constexpr bool ld = LA && m >= LA0 && (m - LA0) % LAS == 0 && (m - LA0) / LAS < 4;
+                    if constexpr (ld) mfma_load_a(integral_constant<int, 4 + r>{}, integral_constant<int, j>{}, AY[r], BF[HP ^ 1][j], integral_constant<int, HP * 4 + (m - LA0) / LAS>{});
+                    else mfma(integral_constant<int, 4 + r>{}, integral_constant<int, j>{}, AY[r], BF[HP ^ 1][j]);
+                    MOE_FENCE();
+                    if (m < NF1) {
+                        if (m == 1) fetch_a(HP, 0, AX[0]);
+                        else if (m > NJ) fetch_a(HP, m - NJ, AX[m - NJ]);
+                        else fetch_b(st, HP, m == 0 ? 0 : m - 1);
+                        MOE_FENCE();
+                    }
+                });
+                constexpr int LB0 = NB == 2 ? 8 : 6, LBS = NB == 2 ? 6 : 5;             // MFMAs with a weight load behind them
+                static_for<NMF>([&](auto mc) __attribute__((always_inline)) {
+                    constexpr int m = decltype(mc)::value;
+                    constexpr int r = m / NJ, j = m % NJ;
+                    constexpr bool ld = LB && m >= LB0 && (m - LB0) % LBS == 0 && (m - LB0) / LBS < 2 * NB;
+                    if constexpr (ld) mfma_load_b(integral_constant<int, r>{}, integral_constant<int, j>{}, AX[r], BF[HP][j], integral_constant<int, nslot>{}, integral_constant<int, (m - LB0) / LBS>{}, kn);
+                    else mfma(integral_constant<int, r>{}, integral_constant<int, j>{}, AX[r], BF[HP][j]);
+                    MOE_FENCE();
+                    if (m < 4) {
+                        fetch_a(HP, 4 + m, AY[m]);
+                        MOE_FENCE();
+                    }
+                });
+            } else {
+                constexpr int NH = NJ / 2, NG = 4 * NH;             // column fragments and MFMAs of a group
+                constexpr int NF1 = NJ + 4;                         // fetches of group 1: B0, A0, B1 .. B(NJ-1), A1, A2, A3
+                constexpr int LA0 = NB == 2 ? 12 : 4;               // MFMAs LA0 .. LA0 + 3 have an activation load behind them
+                static_for<NG>([&](auto mc) __attribute__((always_inline)) {
+                    constexpr int m = decltype(mc)::value;
+                    constexpr int r = m / NH, j = NH + m % NH;
+                    constexpr bool ld = LA && HP == 0 && m >= LA0 && m < LA0 + 4;
+                    const i32x4& a_prev = HP ? AX[r] : AY[r];       // half-step k-1 used the other set
+                    if constexpr (ld) mfma_load_a(integral_constant<int, r>{}, integral_constant<int, j>{}, a_prev, BF[HP ^ 1][j], integral_constant<int, m - LA0>{});
+                    else mfma(integral_constant<int, r>{}, integral_constant<int, j>{}, a_prev, BF[HP ^ 1][j]);
+                    MOE_FENCE();
+                    if (m < NF1) {
+                        if (m == 1) fetch_a(HP, 0, HP ? AY[0] : AX[0]);
+                        else if (m > NJ) fetch_a(HP, m - NJ, HP ? AY[m - NJ] : AX[m - NJ]);
+                        else fetch_b(st, HP, m == 0 ? 0 : m - 1);
+                        MOE_FENCE();
+                    }
+                });
+                constexpr int LB0 = 2, LBS = NB == 2 ? 4 : 3;       // MFMAs with a weight load behind them
+                static_for<NG>([&](auto mc) __attribute__((always_inline)) {
+                    constexpr int m = decltype(mc)::value;
+                    constexpr int r = m / NH, j = m % NH;
+                    constexpr bool ld = LB && m >= LB0 && (m - LB0) % LBS == 0 && (m - LB0) / LBS < 2 * NB;
+                    const i32x4& a_cur = HP ? AY[r] : AX[r];
+                    if constexpr (ld) mfma_load_b(integral_constant<int, r>{}, integral_constant<int, j>{}, a_cur, BF[HP][j], integral_constant<int, nslot>{}, integral_constant<int, (m - LB0) / LBS>{}, kn);
+                    else mfma(integral_constant<int, r>{}, integral_constant<int, j>{}, a_cur, BF[HP][j]);
+                    MOE_FENCE();
+                });
+                if (LA && HP) {            // the k-step two ahead has no second load part: its sources move on here
+                    a_ptr += kARowB;
+                    a_wr = (a_wr == kRingA + (kStagesA - 1) * kStageA) ? kRingA : a_wr + kStageA;
+                    a_wr_w = (a_wr_w == a_wr_last) ? lds_wave + kRingA : a_wr_w + kStageA;
+                }
+            }
+            if (HP) {                          // the next half-step reads the next activation stage
+                const int d = (a_rd == kStagesA - 1) ? -(kStagesA - 1) * kStageA : kStageA;
+                a_rd = (a_rd == kStagesA - 1) ? 0 : a_rd + 1;
+                a_frag[0] += d;
+                a_frag[1] += d;
+            }
+        };
+
+        constexpr int kLB = 2 * NB;                       // weight loads of a half-step
+        constexpr int kL2 = HALF ? 4 + 2 * kLB : 2 * (4 + kLB);    // loads of two consecutive half-steps
         const std::true_type L{};
         const std::false_type N{};
         // prologue, in the order the half-steps -4 .. -1 would have issued them: activation k-steps
@@ -423,51 +465,74 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         for (int i = 0; i < 4; ++i) load_a(0, i);
 #pragma unroll
         for (int s = 0; s < S - 1; ++s) {
+            if (!HALF || ((s + 1) & 1) == 0) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) load_a((s + 1) & 1, i);
+                for (int i = 0; i < 4; ++i) load_a((s + 1) & 1, i);
+            } else {
+                advance_a(7);
+            }
 #pragma unroll
-            for (int i = 0; i < 2 * NB; ++i) load_b(s, s, s & 1, i);
+            for (int i = 0; i < kLB; ++i) load_b(s, s, s & 1, i);
         }
         int k = 0;
         for (; k + S < KH; k += S) {
-            half_step(k, integral_constant<int, 0>{}, L, L, integral_constant<int, 2 * kL>{});
-            half_step(k + 1, integral_constant<int, 1>{}, L, L, integral_constant<int, 2 * kL>{});
-            half_step(k + 2, integral_constant<int, 2>{}, L, L, integral_constant<int, 2 * kL>{});
-            half_step(k + 3, integral_constant<int, 3>{}, L, L, integral_constant<int, 2 * kL>{});
+            half_step(k, integral_constant<int, 0>{}, L, L, integral_constant<int, kL2>{});
+            half_step(k + 1, integral_constant<int, 1>{}, L, L, integral_constant<int, kL2>{});
+            half_step(k + 2, integral_constant<int, 2>{}, L, L, integral_constant<int, kL2>{});
+            half_step(k + 3, integral_constant<int, 3>{}, L, L, integral_constant<int, kL2>{});
         }
         // last four half-steps: one more weight stage to load, then the rings drain
-        half_step(k, integral_constant<int, 0>{}, N, L, integral_constant<int, 2 * kL>{});
-        half_step(k + 1, integral_constant<int, 1>{}, N, N, integral_constant<int, kL + 2 * NB>{});
-        half_step(k + 2, integral_constant<int, 2>{}, N, N, integral_constant<int, 2 * NB>{});
+        half_step(k, integral_constant<int, 0>{}, N, L, integral_constant<int, kL2>{});
+        half_step(k + 1, integral_constant<int, 1>{}, N, N, integral_constant<int, (HALF ? 0 : 4) + 2 * kLB>{});
+        half_step(k + 2, integral_constant<int, 2>{}, N, N, integral_constant<int, kLB>{});
         half_step(k + 3, integral_constant<int, 3>{}, N, N, integral_constant<int, 0>{});
-        // row tiles 4..7 of the last half-step (weight fragment set 1: KH is even)
+        // the rotated group of the last half-step (weight fragment set 1: KH is even)
         __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
-        static_for<NMF>([&](auto mc) __attribute__((always_inline)) { mfma(integral_constant<int, 1>{}, integral_constant<int, 1>{}, mc); });
+        if constexpr (!HALF) {
+            static_for<NMF>([&](auto mc) __attribute__((always_inline)) {
+                constexpr int m = decltype(mc)::value;
+                mfma(integral_constant<int, 4 + m / NJ>{}, integral_constant<int, m % NJ>{}, AY[m / NJ], BF[1][m % NJ]);
+            });
+        } else {
+            static_for<2 * NJ>([&](auto mc) __attribute__((always_inline)) {
+                constexpr int m = decltype(mc)::value;
+                constexpr int NH = NJ / 2;
+                mfma(integral_constant<int, m / NH>{}, integral_constant<int, NH + m % NH>{}, AY[m / NH], BF[1][NH + m % NH]);
+            });
+        }
         mfma_drain();
     };
     MOE_TL(2);
-    // A row tile whose last rows are missing runs the same loop on repeated rows: skipping the MFMA
-    // tiles without a valid row takes a branch per MFMA (a wavefront issues about one instruction in
-    // four clocks, and the branches cost more than the 16 clocks of the MFMA they skip).
-    main_loop();
+    // A row tile with at most 128 rows takes the half-height loop; any other whose last rows are missing
+    // runs the full loop on repeated rows (skipping single MFMAs would take a branch each: a wavefront
+    // issues about one instruction in four clocks, and the branches cost more than the MFMAs they skip).
+    const bool half_tile = rows_here <= 128;
+    if (half_tile) main_loop(std::true_type{});
+    else main_loop(std::false_type{});
     MOE_TL(3);
 
     // ---- epilogue ---------------------------------------------------------------------
     // accumulator register r of lane l in MFMA tile (i, j) is the element at row i*16 + (l/16)*4 + r,
     // column l%16 of that 16 x 16 tile
     const int col_l = lane & 15;
-    const int a_row_base = wm * 128 + (lane >> 4) * 4;
+    const int a_row_base = wm * (half_tile ? 64 : 128) + (lane >> 4) * 4;
     const bool full_rows = rows_here == BM;
+    // store(i, v): the 4 x NJ x 16 values of row tile i of this wavefront
+    auto for_row_tiles = [&](auto n_c, auto&& store) __attribute__((always_inline)) {
+        static_for<decltype(n_c)::value>([&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value;
+            float v[NJ][4];
+            static_for<NJ * 4>([&](auto c) __attribute__((always_inline)) {
+                constexpr int q = decltype(c)::value;
+                v[q >> 2][q & 3] = acc_read<i * NJ * 4 + q>();
+            });
+            store(i, v);
+        });
+    };
     if (MODE == 0) {
         __bf16* h = (__bf16*)p.out + (int64_t)row0 * p.ldo + nt * 128 + wn * 64 + col_l;
-        auto store_rows = [&](auto full) __attribute__((always_inline)) {
-            static_for<8>([&](auto ic) __attribute__((always_inline)) {
-                constexpr int i = decltype(ic)::value;
-                float v[NJ][4];
-                static_for<NJ * 4>([&](auto c) __attribute__((always_inline)) {
-                    constexpr int q = decltype(c)::value;
-                    v[q >> 2][q & 3] = acc_read<i * NJ * 4 + q>();
-                });
+        auto store_rows = [&](auto full, auto n_c) __attribute__((always_inline)) {
+            for_row_tiles(n_c, [&](int i, float (&v)[NJ][4]) __attribute__((always_inline)) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int row = a_row_base + i * 16 + r;
@@ -479,8 +544,9 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                 }
             });
         };
-        if (full_rows) store_rows(std::true_type{});
-        else store_rows(std::false_type{});
+        if (full_rows) store_rows(std::true_type{}, std::integral_constant<int, 8>{});
+        else if (half_tile) store_rows(std::false_type{}, std::integral_constant<int, 4>{});
+        else store_rows(std::false_type{}, std::integral_constant<int, 8>{});
     } else {
         // the 256 row weights of the tile go through LDS (free now): one load per thread instead of
         // one dependent global load per accumulator row
@@ -491,14 +557,8 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         const int d0 = nt * (128 * NB) + wn * (16 * NJ);   // n_cols is a multiple of 128: with NB = 2 a wavefront's columns are all valid or all not
         if (d0 < p.n_cols) {
             float* o = (float*)p.out + (int64_t)row0 * p.ldo + d0 + col_l;
-            auto store_rows = [&](auto full) __attribute__((always_inline)) {
-                static_for<8>([&](auto ic) __attribute__((always_inline)) {
-                    constexpr int i = decltype(ic)::value;
-                    float v[NJ][4];
-                    static_for<NJ * 4>([&](auto c) __attribute__((always_inline)) {
-                        constexpr int q = decltype(c)::value;
-                        v[q >> 2][q & 3] = acc_read<i * NJ * 4 + q>();
-                    });
+            auto store_rows = [&](auto full, auto n_c) __attribute__((always_inline)) {
+                for_row_tiles(n_c, [&](int i, float (&v)[NJ][4]) __attribute__((always_inline)) {
                     const int rowq = a_row_base + i * 16;      // 4 consecutive rows
                     const float4 wq = *(const float4*)(sw + rowq);
                     const float w4[4] = {wq.x, wq.y, wq.z, wq.w};
@@ -513,8 +573,9 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                     }
                 });
             };
-            if (full_rows) store_rows(std::true_type{});
-            else store_rows(std::false_type{});
+            if (full_rows) store_rows(std::true_type{}, std::integral_constant<int, 8>{});
+            else if (half_tile) store_rows(std::false_type{}, std::integral_constant<int, 4>{});
+            else store_rows(std::false_type{}, std::integral_constant<int, 8>{});
         }
     }
     MOE_TL(4);
