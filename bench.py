@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM traffic per launch of the gate/up GEMM on the default workload, in bytes, from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/ (None: not measured).
-MEASURED_TRAFFIC = {"c3_mixtral8x7b_t4096": 3.784e9}
+MEASURED_TRAFFIC = {"c3_mixtral8x7b_t4096": 6.905e9}
 
 
 def main():

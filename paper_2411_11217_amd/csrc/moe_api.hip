@@ -17,8 +17,9 @@ static int g_opts[OPT_COUNT] = {
     /*OPT_XCD_REMAP*/ 1,     // 1: the column tiles of the expert GEMMs are dealt round robin to the 8 XCDs
     /*OPT_PROFILE*/ 0,       // 1: moe_layer records stage events (see moe_profile_read)
     /*OPT_DOWN_COLS*/ 0,     // column tiles of the bf16 down GEMM: 0 = by grid size, 1 = 128 wide, 2 = 256 wide
+    /*OPT_HALF_TILES*/ 1,    // 1: bf16 row tiles with at most 128 rows run the half-height loop
 };
-static const char* g_opt_names[OPT_COUNT] = {"xcd_remap", "profile", "down_cols"};
+static const char* g_opt_names[OPT_COUNT] = {"xcd_remap", "profile", "down_cols", "half_tiles"};
 int get_opt(int id) { return g_opts[id]; }
 
 int validate_shape(const moe_shape* s) {

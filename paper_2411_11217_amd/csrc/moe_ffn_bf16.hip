@@ -506,7 +506,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     // A row tile with at most 128 rows takes the half-height loop; any other whose last rows are missing
     // runs the full loop on repeated rows (skipping single MFMAs would take a branch each: a wavefront
     // issues about one instruction in four clocks, and the branches cost more than the MFMAs they skip).
-    const bool half_tile = rows_here <= 128;
+    const bool half_tile = p.half_tiles && rows_here <= 128;
     if (half_tile) main_loop(std::true_type{});
     else main_loop(std::false_type{});
     MOE_TL(3);
@@ -649,6 +649,7 @@ int launch_linear_bf16(const LinearArgs& a, hipStream_t st) {
     p.row_w = nullptr;
     p.status = a.status;
     p.xcd_remap = get_opt(OPT_XCD_REMAP);
+    p.half_tiles = get_opt(OPT_HALF_TILES);
     const int wide_tiles = (p.n_page_tiles + 1) / 2;
     if ((int64_t)(a.T / BM + 1) * wide_tiles < 2 * kComputeUnits) {       // too few 256-wide tiles to fill the chip
         p.NT = p.n_page_tiles;

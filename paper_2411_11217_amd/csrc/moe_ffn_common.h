@@ -30,6 +30,7 @@ struct GemmParams {
     const float* row_w;
     int32_t* status;
     int32_t xcd_remap;
+    int32_t half_tiles;       // bf16 kernel: row tiles with at most 128 rows run the half-height loop
 };
 
 struct TileCoord {
@@ -134,6 +135,7 @@ inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const 
     p.table_row_mod = a.table_row_mod;
     p.status = a.status;
     p.xcd_remap = get_opt(OPT_XCD_REMAP);
+    p.half_tiles = get_opt(OPT_HALF_TILES);
 }
 
 // parameters of the gate/up launch (K = H, output h[R][F]) and of the down launch

@@ -40,7 +40,7 @@ class Hardware:
 # (expert GEMMs on the 4096-token Mixtral-8x7B-shaped layer, weight streaming on the 256-token
 # one, page copies from pinned host memory).
 MI355X_PEAK = Hardware(p_g=2.5e15, b_g=8.0e12, b_cg=64e9)
-MI355X_MEASURED = Hardware(p_g=1.05e15, b_g=5.0e12, b_cg=55.7e9)
+MI355X_MEASURED = Hardware(p_g=1.24e15, b_g=5.5e12, b_cg=55.7e9)
 
 
 @dataclasses.dataclass(frozen=True)

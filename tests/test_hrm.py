@@ -77,18 +77,20 @@ def test_crossover_micro_batch_is_the_ridge():
 
 # (layer, N, mu, r_w, measured ms per layer on one MI355X; bench.py and bench.py --pipeline)
 MEASURED = [
-    (hrm.MIXTRAL_8X7B, 256, 256, 1.0, 0.607),
-    (hrm.MIXTRAL_8X7B, 4096, 4096, 1.0, 2.84),
-    (hrm.DBRX, 16384, 4096, 0.0, 115.4),
-    (hrm.DBRX, 16384, 4096, 48 / 95, 59.0),
-    (hrm.DBRX, 16384, 4096, 76 / 95, 26.7),
+    (hrm.MIXTRAL_8X7B, 256, 256, 1.0, 0.573, 0.10),
+    (hrm.MIXTRAL_8X7B, 4096, 4096, 1.0, 2.44, 0.10),
+    (hrm.MIXTRAL_8X22B, 8192, 8192, 1.0, 7.80, 0.10),
+    (hrm.DBRX, 16384, 4096, 0.0, 115.3, 0.10),
+    (hrm.DBRX, 16384, 4096, 48 / 95, 59.0, 0.10),
+    # next to the turning point (link time = GPU time) the copies and the kernels slow each other down
+    (hrm.DBRX, 16384, 4096, 76 / 95, 26.2, 0.15),
 ]
 
 
-@pytest.mark.parametrize("layer,N,mu,r_w,measured_ms", MEASURED)
-def test_model_with_measured_rates_predicts_the_measured_latency(layer, N, mu, r_w, measured_ms):
+@pytest.mark.parametrize("layer,N,mu,r_w,measured_ms,tol", MEASURED)
+def test_model_with_measured_rates_predicts_the_measured_latency(layer, N, mu, r_w, measured_ms, tol):
     r = hrm.layer_latency(layer, hrm.MI355X_MEASURED, N, mu, r_w)
-    assert r["T"] * 1e3 == pytest.approx(measured_ms, rel=0.10)
+    assert r["T"] * 1e3 == pytest.approx(measured_ms, rel=tol)
     # and the nominal peaks are an upper bound on what was measured
     assert hrm.layer_latency(layer, hrm.MI355X_PEAK, N, mu, r_w)["T"] * 1e3 < measured_ms
 
@@ -97,8 +99,8 @@ def test_policy_search_respects_memory_and_finds_the_balance():
     L = hrm.DBRX
     # plenty of GPU memory: compute bound, with the smallest resident fraction that gets there
     pol, rec = hrm.best_policy(L, hrm.MI355X_MEASURED, 16384, [1024, 4096], n_layers=40)
-    assert rec["bound"] == "gpu" and pol["r_w"] == 0.8
-    assert hrm.layer_latency(L, hrm.MI355X_MEASURED, 16384, pol["mu"], 0.75)["bound"] == "link"
+    assert rec["bound"] == "gpu" and pol["r_w"] == pytest.approx(0.85)
+    assert hrm.layer_latency(L, hrm.MI355X_MEASURED, 16384, pol["mu"], 0.80)["bound"] == "link"
     # 96 GB for 40 layers (236 GiB of weights): only part fits; the search keeps as much resident as fits
     small = hrm.Hardware(p_g=1.05e15, b_g=5.0e12, b_cg=55.7e9, m_g=96e9)
     pol, rec = hrm.best_policy(L, small, 16384, [1024, 4096], n_layers=40)
