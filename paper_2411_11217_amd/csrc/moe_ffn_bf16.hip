@@ -348,20 +348,26 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     //            fragments of k and the activation fragments of row tiles 0..3; issues the activation loads;
     //   group 2: row tiles 0..3 of half-step k; fetches the activation fragments of row tiles 4..7;
     //            issues the weight loads.
-    // At most 128 rows: wavefront (wm, wn) owns rows wm*64 .. +63, four row tiles; the two fragment sets
-    // alternate between half-steps, and the groups split the columns instead:
+    // Short tiles.  At most 128 rows: wavefront (wm, wn) owns rows wm*64 .. +63, four row tiles; the two
+    // fragment sets alternate between half-steps, and the groups split the columns instead:
     //   group 1: the second half of the column fragments of half-step k-1; fetches all fragments of k;
     //            issues the activation loads (even half-steps only: rows 128..255 are not loaded at all);
     //   group 2: the first half of the column fragments of half-step k; issues the weight loads.
-    // Such a tile costs about half the MFMAs and three quarters of the loads of a full one.
+    // At most 64 rows: the same with the wavefronts wm = 1 taking part in the loads only; at most 32
+    // rows: two row tiles instead of four.  Measured in cycles of a full tile: 0.6 for the first, and
+    // the launches of the Mixtral-8x7B-shaped workload (whose short tiles have 4 to 31 rows) got 2-3 %
+    // shorter with the other two: under the power limit every MFMA on repeated rows costs time.
     // LA / LB: issue the activation / weight loads of this half-step.  WAITN: my loads that may still
     // be in flight when the stages of half-step k must be complete (those issued during the two
     // half-steps before).  Weight fragment set U & 1 belongs to half-step k: S is even, so the parity of
     // k is static too.
-    auto main_loop = [&](auto half_tile_c) __attribute__((always_inline)) {
+    auto main_loop = [&](auto half_tile_c, auto rt_c, auto na_c) __attribute__((always_inline)) {
         using std::integral_constant;
         constexpr bool HALF = decltype(half_tile_c)::value;
+        constexpr int RT = decltype(rt_c)::value;       // short tiles: row tiles a wavefront computes (4, 2)
+        constexpr int NA = decltype(na_c)::value;       // short tiles: activation load instructions per k-step (4, 2, 1: 32 rows each)
         constexpr int WROWS = HALF ? 64 : 128;          // rows of a wavefront
+        const bool wact = !HALF || wm == 0 || rows_here > 64;    // a short tile with at most 64 rows is the upper wavefronts' alone
         int a_frag[2];                    // includes the activation stage being read: moves on after every odd half-step
 #pragma unroll
         for (int hp = 0; hp < 2; ++hp)
@@ -412,40 +418,51 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                         MOE_FENCE();
                     }
                 });
-            } else {
-                constexpr int NH = NJ / 2, NG = 4 * NH;             // column fragments and MFMAs of a group
-                constexpr int NF1 = NJ + 4;                         // fetches of group 1: B0, A0, B1 .. B(NJ-1), A1, A2, A3
-                constexpr int LA0 = NB == 2 ? 12 : 4;               // MFMAs LA0 .. LA0 + 3 have an activation load behind them
+            } else if (wact) {
+                constexpr int NH = NJ / 2, NG = RT * NH;            // column fragments and MFMAs of a group
+                constexpr int NF1 = NJ + RT;                        // fetches of group 1: B0, A0, B1 .. B(NJ-1), A1 .. A(RT-1)
                 static_for<NG>([&](auto mc) __attribute__((always_inline)) {
                     constexpr int m = decltype(mc)::value;
                     constexpr int r = m / NH, j = NH + m % NH;
-                    constexpr bool ld = LA && HP == 0 && m >= LA0 && m < LA0 + 4;
+                    constexpr bool ld = LA && HP == 0 && m >= NG - NA;              // the last NA MFMAs have an activation load behind them
                     const i32x4& a_prev = HP ? AX[r] : AY[r];       // half-step k-1 used the other set
-                    if constexpr (ld) mfma_load_a(integral_constant<int, r>{}, integral_constant<int, j>{}, a_prev, BF[HP ^ 1][j], integral_constant<int, m - LA0>{});
+                    if constexpr (ld) mfma_load_a(integral_constant<int, r>{}, integral_constant<int, j>{}, a_prev, BF[HP ^ 1][j], integral_constant<int, ld ? m - (NG - NA) : 0>{});
                     else mfma(integral_constant<int, r>{}, integral_constant<int, j>{}, a_prev, BF[HP ^ 1][j]);
                     MOE_FENCE();
-                    if (m < NF1) {
-                        if (m == 1) fetch_a(HP, 0, HP ? AY[0] : AX[0]);
-                        else if (m > NJ) fetch_a(HP, m - NJ, HP ? AY[m - NJ] : AX[m - NJ]);
-                        else fetch_b(st, HP, m == 0 ? 0 : m - 1);
-                        MOE_FENCE();
-                    }
+                    static_for<NF1>([&](auto fc) __attribute__((always_inline)) {    // the fetches, spread evenly behind the MFMAs
+                        constexpr int f = decltype(fc)::value;
+                        if constexpr (f * NG / NF1 == m) {
+                            if (f == 1) fetch_a(HP, 0, HP ? AY[0] : AX[0]);
+                            else if (f > NJ) fetch_a(HP, f - NJ, HP ? AY[f - NJ] : AX[f - NJ]);
+                            else fetch_b(st, HP, f == 0 ? 0 : f - 1);
+                            MOE_FENCE();
+                        }
+                    });
                 });
-                constexpr int LB0 = 2, LBS = NB == 2 ? 4 : 3;       // MFMAs with a weight load behind them
+                constexpr int LBS = NG / (2 * NB);                  // every LBS-th MFMA has a weight load behind it
                 static_for<NG>([&](auto mc) __attribute__((always_inline)) {
                     constexpr int m = decltype(mc)::value;
                     constexpr int r = m / NH, j = m % NH;
-                    constexpr bool ld = LB && m >= LB0 && (m - LB0) % LBS == 0 && (m - LB0) / LBS < 2 * NB;
+                    constexpr bool ld = LB && m % LBS == 0 && m / LBS < 2 * NB;
                     const i32x4& a_cur = HP ? AY[r] : AX[r];
-                    if constexpr (ld) mfma_load_b(integral_constant<int, r>{}, integral_constant<int, j>{}, a_cur, BF[HP][j], integral_constant<int, nslot>{}, integral_constant<int, (m - LB0) / LBS>{}, kn);
+                    if constexpr (ld) mfma_load_b(integral_constant<int, r>{}, integral_constant<int, j>{}, a_cur, BF[HP][j], integral_constant<int, nslot>{}, integral_constant<int, ld ? m / LBS : 0>{}, kn);
                     else mfma(integral_constant<int, r>{}, integral_constant<int, j>{}, a_cur, BF[HP][j]);
                     MOE_FENCE();
                 });
-                if (LA && HP) {            // the k-step two ahead has no second load part: its sources move on here
-                    a_ptr += kARowB;
-                    a_wr = (a_wr == kRingA + (kStagesA - 1) * kStageA) ? kRingA : a_wr + kStageA;
-                    a_wr_w = (a_wr_w == a_wr_last) ? lds_wave + kRingA : a_wr_w + kStageA;
+            } else {                           // a wavefront without rows only takes its part in the loads
+                if (LA && HP == 0) {
+#pragma unroll
+                    for (int i = 0; i < NA; ++i) load_a(0, i);
                 }
+                if (LB) {
+#pragma unroll
+                    for (int i = 0; i < 2 * NB; ++i) load_b(nslot, kn, nslot & 1, i);
+                }
+            }
+            if (HALF && LA && HP) {            // a short tile has no second load part: the sources of the k-step two ahead move on here
+                a_ptr += kARowB;
+                a_wr = (a_wr == kRingA + (kStagesA - 1) * kStageA) ? kRingA : a_wr + kStageA;
+                a_wr_w = (a_wr_w == a_wr_last) ? lds_wave + kRingA : a_wr_w + kStageA;
             }
             if (HP) {                          // the next half-step reads the next activation stage
                 const int d = (a_rd == kStagesA - 1) ? -(kStagesA - 1) * kStageA : kStageA;
@@ -456,18 +473,18 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         };
 
         constexpr int kLB = 2 * NB;                       // weight loads of a half-step
-        constexpr int kL2 = HALF ? 4 + 2 * kLB : 2 * (4 + kLB);    // loads of two consecutive half-steps
+        constexpr int kL2 = HALF ? NA + 2 * kLB : 2 * (4 + kLB);   // loads of two consecutive half-steps
         const std::true_type L{};
         const std::false_type N{};
         // prologue, in the order the half-steps -4 .. -1 would have issued them: activation k-steps
         // 0 and 1, weight half-steps 0 .. 2 (KH is a multiple of 4 and at least 4)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) load_a(0, i);
+        for (int i = 0; i < (HALF ? NA : 4); ++i) load_a(0, i);
 #pragma unroll
         for (int s = 0; s < S - 1; ++s) {
             if (!HALF || ((s + 1) & 1) == 0) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) load_a((s + 1) & 1, i);
+                for (int i = 0; i < (HALF ? NA : 4); ++i) load_a((s + 1) & 1, i);
             } else {
                 advance_a(7);
             }
@@ -493,8 +510,8 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                 constexpr int m = decltype(mc)::value;
                 mfma(integral_constant<int, 4 + m / NJ>{}, integral_constant<int, m % NJ>{}, AY[m / NJ], BF[1][m % NJ]);
             });
-        } else {
-            static_for<2 * NJ>([&](auto mc) __attribute__((always_inline)) {
+        } else if (wact) {
+            static_for<RT * (NJ / 2)>([&](auto mc) __attribute__((always_inline)) {
                 constexpr int m = decltype(mc)::value;
                 constexpr int NH = NJ / 2;
                 mfma(integral_constant<int, m / NH>{}, integral_constant<int, NH + m % NH>{}, AY[m / NH], BF[1][NH + m % NH]);
@@ -506,9 +523,16 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     // A row tile with at most 128 rows takes the half-height loop; any other whose last rows are missing
     // runs the full loop on repeated rows (skipping single MFMAs would take a branch each: a wavefront
     // issues about one instruction in four clocks, and the branches cost more than the MFMAs they skip).
+    // Short tiles: at most 128 rows: both wavefront rows, 64 rows each; at most 64: the upper wavefront row
+    // alone (the other wavefronts only load); at most 32: two row tiles instead of four.
     const bool half_tile = p.half_tiles && rows_here <= 128;
-    if (half_tile) main_loop(std::true_type{});
-    else main_loop(std::false_type{});
+    using std::integral_constant;
+    if (!half_tile) main_loop(std::false_type{}, integral_constant<int, 4>{}, integral_constant<int, 4>{});
+    else if (rows_here > 64) main_loop(std::true_type{}, integral_constant<int, 4>{}, integral_constant<int, 4>{});
+    else if (rows_here > 32) main_loop(std::true_type{}, integral_constant<int, 4>{}, integral_constant<int, 2>{});
+    else main_loop(std::true_type{}, integral_constant<int, 2>{}, integral_constant<int, 1>{});
+    const bool wact = !half_tile || wm == 0 || rows_here > 64;        // this wavefront has rows
+    const int row_tiles = !half_tile ? 8 : (rows_here > 32 ? 4 : 2);   // and this many row tiles
     MOE_TL(3);
 
     // ---- epilogue ---------------------------------------------------------------------
@@ -545,7 +569,9 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
             });
         };
         if (full_rows) store_rows(std::true_type{}, std::integral_constant<int, 8>{});
-        else if (half_tile) store_rows(std::false_type{}, std::integral_constant<int, 4>{});
+        else if (!wact) {
+        } else if (row_tiles == 2) store_rows(std::false_type{}, std::integral_constant<int, 2>{});
+        else if (row_tiles == 4) store_rows(std::false_type{}, std::integral_constant<int, 4>{});
         else store_rows(std::false_type{}, std::integral_constant<int, 8>{});
     } else {
         // the 256 row weights of the tile go through LDS (free now): one load per thread instead of
@@ -574,7 +600,9 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                 });
             };
             if (full_rows) store_rows(std::true_type{}, std::integral_constant<int, 8>{});
-            else if (half_tile) store_rows(std::false_type{}, std::integral_constant<int, 4>{});
+            else if (!wact) {
+            } else if (row_tiles == 2) store_rows(std::false_type{}, std::integral_constant<int, 2>{});
+            else if (row_tiles == 4) store_rows(std::false_type{}, std::integral_constant<int, 4>{});
             else store_rows(std::false_type{}, std::integral_constant<int, 8>{});
         }
     }

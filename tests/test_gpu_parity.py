@@ -95,6 +95,34 @@ def run_layer(case: Case, ref=None):
     return y, ws
 
 
+@pytest.mark.parametrize("down_cols", [0, 2])
+def test_expert_ffn_row_counts_across_the_tile_variants(down_cols):
+    """Segments of 1 .. 300 rows, one per expert, on both sides of every threshold of the bf16 kernel's row-tile
+    variants (32, 64, 128 rows and the 256-row tile boundary) and an empty one, against the oracle row by row."""
+    counts = [1, 16, 17, 32, 33, 0, 64, 65, 127, 128, 129, 255, 256, 257, 300, 31]
+    E, H, F = len(counts), 256, 384
+    cfg = MoEConfig("rows", "bf16", T=sum(counts), H=H, F=F, E=E, k=1, page_bytes=64 * 1024, seed=77)
+    case = Case(cfg, shuffle_pages=True, extra_pages=1)
+    offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    v = case.view
+    x_bits = v["x"]                                     # [T, H] in the oracle's storage form; k = 1: rows are tokens
+    h_ref, o_ref = oracle.expert_ffn(x_bits, offsets, v["W1"], v["W3"], v["W2"], cfg.dtype_code)
+    M.set_option("down_cols", down_cols)
+    try:
+        status = torch.zeros(4, dtype=torch.int32, device="cuda")
+        h, out = M.moe_expert_ffn(case.shape, case.x, _dev_i32(offsets), case.pw.table_dev, case.pw.pages_dev, status=status)
+        torch.cuda.synchronize()
+    finally:
+        M.set_option("down_cols", 0)
+    assert status.cpu().tolist() == [0, 0, 0, 0]
+    for e, c in enumerate(counts):
+        if c == 0:
+            continue
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        assert_h_close(h.float().cpu().numpy()[lo:hi], h_ref[lo:hi], "bf16", f"h, expert {e} with {c} rows")
+        assert_close(out.cpu().numpy()[lo:hi], o_ref[lo:hi], "bf16", f"out, expert {e} with {c} rows")
+
+
 def test_c1_stagewise_and_layer():
     case = Case(C1)
     ref = run_stagewise(case)
