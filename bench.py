@@ -22,6 +22,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak, TFLOP/s
 PEAK_HBM_GBS = 8000.0
+PEAK_CLOCK_MHZ = 2400.0       # the clock the published peaks are quoted at
 
 # HBM traffic per launch of the gate/up GEMM on the default workload, in bytes, from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/ (None: not measured).
@@ -134,6 +135,12 @@ def main():
                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get(args.config),
                     "avg_launch_ms": round(stages["gemm_gate_up"], 4), "launches_timed": n_prof}
+        # the shader clock a block of the launch saw (the chip is power limited under this kernel; the
+        # published peak is for 2400 MHz), and the fraction of the peak at that clock
+        st = ws.view("status").cpu().tolist()
+        if cfg.dtype == "bf16" and st[2] > 0:
+            roofline["clock_mhz"] = {"gate_up": st[2], "down": st[3]}
+            roofline["frac_at_that_clock"] = round(achieved / (PEAK_BF16_TFLOPS * st[2] / PEAK_CLOCK_MHZ), 4)
     extra = {}
     if stages:
         t_ffn = (stages["gemm_gate_up"] + stages["gemm_down"]) * 1e-3

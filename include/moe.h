@@ -112,7 +112,8 @@ int moe_page_table_validate(const moe_shape* s, const int32_t* page_table_host, 
 
 typedef struct moe_workspace_layout {
     /* byte offsets into the workspace of moe_layer, each 256-byte aligned */
-    size_t status;     /* int32[4]: [0] bit 0 = a page-table entry was not resident */
+    size_t status;     /* int32[4]: [0] bit 0 = a page-table entry was not resident; [2], [3]: shader clock in MHz that a
+                        * block of the bf16 gate/up and down launch saw (diagnostic, 0 if none reported) */
     size_t topk_ids;   /* int32[T][k] */
     size_t topk_w;     /* float[T][k] */
     size_t counts;     /* int32[E] */
@@ -156,7 +157,7 @@ int moe_permute(const moe_shape* s, const int32_t* topk_ids, const float* topk_w
  * and out[r] *= row_w[r] when row_w != NULL.  x_perm: device dtype[R][H];
  * offsets: device int32[E+1]; page_table: device int32[E][pages_per_expert];
  * page_pool: device, pool_pages * page_bytes; h_ws: device dtype[R][F];
- * out: device float[R][H]; status: device int32[4] or NULL (see above). */
+ * out: device float[R][H]; status: device int32[4] or NULL (see moe_workspace_layout.status). */
 int moe_expert_ffn(const moe_shape* s, const void* x_perm, const int32_t* offsets,
                    const int32_t* page_table, const void* page_pool, int64_t pool_pages,
                    const float* row_w, void* h_ws, float* out, int32_t* status, void* stream);

@@ -197,6 +197,14 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     // ---- which tile is mine -------------------------------------------------
     const TileCoord tc = locate_tile<BM>(p);
     if (!tc.valid) return;
+    // diagnostic: some blocks report the shader clock they saw (cycle counter against the 100 MHz
+    // constant counter over the whole tile); the chip is power limited under this kernel
+    const bool clock_probe = p.status && (blockIdx.x & 511) == 256 && tid == 0;
+    long long probe_c = 0, probe_w = 0;
+    if (clock_probe) {
+        probe_c = clock64();
+        probe_w = wall_clock64();
+    }
 #ifdef MOE_FFN_TIMELINE
     if (tid == 0) { tl[0] = t_entry; tl[5] = wall_clock64(); tl[7] = 1 + rows_here_tl(tc.rows_here) + ((long long)(__builtin_amdgcn_s_getreg(6164) & 15) << 32); }
 #endif
@@ -610,6 +618,10 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
 #ifdef MOE_FFN_TIMELINE
     if (tid == 0) tl[6] = wall_clock64() - tl[5];
 #endif
+    if (clock_probe) {
+        const long long dc = clock64() - probe_c, dw = wall_clock64() - probe_w;
+        if (dw > 0) p.status[2 + MODE] = (int32_t)(dc * 100 / dw);       // MHz
+    }
     if (bad && tid == 0 && p.status) atomicOr(p.status, 1);
 }
 

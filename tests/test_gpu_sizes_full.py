@@ -13,7 +13,7 @@ import torch
 import oracle
 import paper_2411_11217_amd as M
 from moe_workloads import CONFIGS
-from util import Case, assert_close, assert_h_close, check_permutation_valid, compare_routing, say
+from util import Case, assert_close, assert_h_close, check_permutation_valid, compare_routing, say, assert_status_clean
 
 pytestmark = pytest.mark.gpu
 
@@ -46,7 +46,7 @@ def check_full(case: Case, y: torch.Tensor, ws, label: str):
         assert np.array_equal(pm_gpu[n], pm_ref[n]), n
     say(f"    counts: {pm_gpu['counts'].tolist()}")
     assert pm_gpu["counts"].sum() == cfg.T * cfg.k
-    assert ws.view("status").cpu().tolist() == [0, 0, 0, 0]
+    assert_status_clean(ws.view("status").cpu().tolist())
     yh = y.cpu().numpy()
     assert np.isfinite(yh).all()
 

@@ -142,3 +142,11 @@ def check_permutation_valid(ids: np.ndarray, E: int, k: int, pm: dict):
     assert np.array_equal(offsets[1:], np.cumsum(counts))
     assert np.array_equal(row_src, np.argsort(flat, kind="stable"))
     assert np.array_equal(row_of[row_src], np.arange(R))
+
+
+def assert_status_clean(status):
+    """Status words: [0] error bits and [1] (unused) must be zero; [2], [3] carry the shader clock a block of the
+    bf16 GEMM launches saw (diagnostic, any value)."""
+    st = [int(v) for v in status]
+    assert st[0] == 0 and st[1] == 0, st
+    return st
