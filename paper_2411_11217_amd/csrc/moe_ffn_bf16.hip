@@ -42,8 +42,8 @@
 // utilisation).  The loop is therefore (a) rotated: half of the MFMAs of half-step
 // k-1 are issued AFTER the barrier that opens half-step k, so the matrix cores have
 // work while the wavefronts synchronise and the first operands of k are fetched,
-// and (b) interleaved: between two MFMAs at most one LDS fetch or one global load is
-// issued.  Scheduling fences pin that order.
+// and (b) interleaved: between two MFMAs of a full tile at most one LDS fetch or one
+// global load is issued.  Scheduling fences pin that order.
 //
 // Wavefront w computes rows (w / 2) * 128 .. +127 and, of the 256 columns, for
 // MODE 0 columns (w % 2) * 64 .. +63 of both tiles, for MODE 1 columns
