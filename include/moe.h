@@ -76,12 +76,13 @@ int moe_validate_shape(const moe_shape* s);
  *         is stored at chunk position (c & 8) | ((c & 7) ^ ((n >> 1) & 7)).
  *   bf16: two half-tiles of 8 KiB, one per 32 reduction elements; half-tile c >> 2
  *         holds, in row n of 64 bytes, chunk c (0..7) of that row at chunk position
- *         (c & 3) ^ ((n >> 2) & 3).
+ *         (c & 3) ^ ((n >> 2) & 2).
  * These are the images the GEMM kernels copy straight into LDS (the bf16 kernel
  * consumes 32 reduction elements per pipeline stage).  The LDS has 64 banks of
- * 4 bytes, a 128-bit LDS read executes in phases of 16 lanes, and the XOR with
- * the row index makes every phase of a read of an MFMA operand (one row per lane,
- * same chunk) touch every bank once.  A page holds page_bytes / tile_bytes
+ * 4 bytes, a 128-bit LDS read executes in four phases of 16 lanes (for the bf16
+ * kernel's operand fetch, one row per lane: rows r and r + 8 of two neighbouring
+ * chunks meet in a phase), and the XOR with the row index makes every phase touch
+ * every bank once.  A page holds page_bytes / tile_bytes
  * consecutive tiles and never spans experts.  Expert e owns
  * pages_gu + pages_d logical pages:
  *   group GU (logical pages 0 .. pages_gu-1): tiles ordered [f/128][w][h/64],

@@ -54,10 +54,10 @@ Geom geometry(const moe_shape& s) {
 // ---- packer -------------------------------------------------------------------
 // Byte offset inside a page tile of the 16-byte chunk c of row n (the page format of moe.h).
 // bf16: two half-tiles of 128 rows x 64 bytes, chunk c & 3 of half c >> 2 at position
-// (c & 3) ^ ((n >> 2) & 3).  f32: 128 rows x 256 bytes, chunk c at position
+// (c & 3) ^ ((n >> 2) & 2).  f32: 128 rows x 256 bytes, chunk c at position
 // (c & 8) | ((c & 7) ^ ((n >> 1) & 7)).
 static inline int64_t tile_chunk_offset(int esize, int n, int c) {
-    if (esize == 2) return (int64_t)(c >> 2) * (kTileN * 64) + n * 64 + (((c & 3) ^ ((n >> 2) & 3)) << 4);
+    if (esize == 2) return (int64_t)(c >> 2) * (kTileN * 64) + n * 64 + (((c & 3) ^ ((n >> 2) & 2)) << 4);
     return (int64_t)n * (kTileK * 4) + (((c & 8) | ((c & 7) ^ ((n >> 1) & 7))) << 4);
 }
 

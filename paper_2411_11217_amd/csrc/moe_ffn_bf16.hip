@@ -31,10 +31,14 @@
 //                cores, the longest chain of the loop.  Rows are row-major in HBM; the
 //                lane -> chunk choice of the load applies the swizzle.  The stage of
 //                k-step K + 2 is loaded during the two half-steps of k-step K.
-// Swizzles: in a 64-byte-row stage the 16-byte chunk c of row r sits at position
-// c ^ ((r >> 2) & 3), in a 128-byte-row stage at c ^ ((r >> 1) & 7): 64 banks hold
-// four (two) rows, and this makes every 16-lane phase of a ds_read_b128 of an MFMA
-// operand (one row per lane, same chunk) touch each bank once.
+// Swizzles.  An MFMA operand fetch is a ds_read_b128 with one row per lane (row lane % 16, 16-byte
+// chunk lane / 16).  The 64 banks hold 256 consecutive bytes and the 64 lanes are served in four
+// phases of 16 lanes - but not 16 consecutive lanes: measured with the bank-conflict counter on ten
+// layouts, rows r and r + 8 of two neighbouring chunks meet in a phase.  In a 64-byte-row stage the
+// chunk c of row r therefore sits at position c ^ (2 * ((r >> 3) & 1)) (rows r and r + 8 share a bank
+// row), in a 128-byte-row stage at c ^ ((r >> 1) & 7): both measured free of conflicts, 4 cycles per
+// fetch.  (With c ^ ((r >> 2) & 3), which is right for 16 consecutive lanes and for the lane layout
+// of the 32x32 MFMA, every weight fetch of this kernel took 8 cycles.)
 //
 // Schedule.  Measured on this chip: when all wavefronts issue their loads, then
 // their LDS fetches, then their MFMAs in blocks after each barrier, the matrix
@@ -311,7 +315,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     // LDS byte offsets of this lane's operand chunks: row lane%16 of a 16-row MFMA tile, chunk lane/16
     // of the four a half-step has.  Weights (64-byte rows, one half-step per stage): chunk lane/16;
     // activations (128-byte rows, two half-steps per stage): chunk 4*hp + lane/16 in half-step parity hp.
-    const int b_frag0 = (lane & 15) * kRowB + ((((lane >> 4) ^ ((lane >> 2) & 3)) & 3) << 4);
+    const int b_frag0 = (lane & 15) * kRowB + (((lane >> 4) ^ ((lane >> 2) & 2)) << 4);
     // B fragment j: MODE 0: gate rows wn*64 + (j%4)*16 of tile 0 (j < 4), the same up rows of tile 1 (j >= 4);
     //               MODE 1: rows wn*(16*NJ) + j*16 of the 128*NB rows of the block's tiles
     int b_base[NJ];

@@ -87,12 +87,12 @@ def test_pack_unpack_round_trip_and_layout(dtype):
 
     # documented layout: tile (f/128, w, h/64) of group GU; inside a tile the 16-byte chunk c of row n sits
     # (f32)  in row n of 256 bytes at position (c & 8) | ((c & 7) ^ ((n >> 1) & 7)),
-    # (bf16) in half-tile c >> 2 (8 KiB each), row n of 64 bytes, at position (c & 3) ^ ((n >> 2) & 3)
+    # (bf16) in half-tile c >> 2 (8 KiB each), row n of 64 bytes, at position (c & 3) ^ ((n >> 2) & 2)
     esz = 2 if dtype == "bf16" else 4
 
     def chunk_offset(n, c):
         if dtype == "bf16":
-            return (c >> 2) * 8192 + n * 64 + (((c & 3) ^ ((n >> 2) & 3)) << 4)
+            return (c >> 2) * 8192 + n * 64 + (((c & 3) ^ ((n >> 2) & 2)) << 4)
         return n * 256 + (((c & 8) | ((c & 7) ^ ((n >> 1) & 7))) << 4)
 
     tb = M.tile_bytes(s)
