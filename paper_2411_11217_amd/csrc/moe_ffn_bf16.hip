@@ -309,8 +309,8 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     };
 
     // accumulator tile (i, j), rows wm*128 + i*16, columns by B fragment j: registers a[(i*NJ + j)*4 ..+3]
+    // (zeroed in the main loop, behind the first loads)
     acc_declare<32 * NJ>();
-    static_for<32 * NJ>([&](auto rc) __attribute__((always_inline)) { acc_zero<decltype(rc)::value>(); });
 
     // LDS byte offsets of this lane's operand chunks: row lane%16 of a 16-row MFMA tile, chunk lane/16
     // of the four a half-step has.  Weights (64-byte rows, one half-step per stage): chunk lane/16;
@@ -503,6 +503,8 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
 #pragma unroll
             for (int i = 0; i < kLB; ++i) load_b(s, s, s & 1, i);
         }
+        // the accumulators are cleared while the first stages are on their way
+        static_for<32 * NJ>([&](auto rc) __attribute__((always_inline)) { acc_zero<decltype(rc)::value>(); });
         int k = 0;
         for (; k + S < KH; k += S) {
             half_step(k, integral_constant<int, 0>{}, L, L, integral_constant<int, kL2>{});
