@@ -405,7 +405,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                 constexpr int LA0 = NF1 + (NB == 2 ? 2 : 1), LAS = NB == 2 ? 4 : 2;     // MFMAs with an activation load behind them
                 static_for<NMF>([&](auto mc) __attribute__((always_inline)) {
                     constexpr int m = decltype(mc)::value;
-                    constexpr int r = m / NJ, j = m % NJ;
+                    constexpr int r = m / NJ, j = (r & 1) ? NJ - 1 - m % NJ : m % NJ;   // back and forth: one operand stays at each row change
                     constexpr bool ld = LA && m >= LA0 && (m - LA0) % LAS == 0 && (m - LA0) / LAS < 4;
                     if constexpr (ld) mfma_load_a(integral_constant<int, 4 + r>{}, integral_constant<int, j>{}, AY[r], BF[HP ^ 1][j], integral_constant<int, HP * 4 + (m - LA0) / LAS>{});
                     else mfma(integral_constant<int, 4 + r>{}, integral_constant<int, j>{}, AY[r], BF[HP ^ 1][j]);
@@ -420,7 +420,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                 constexpr int LB0 = NB == 2 ? 8 : 6, LBS = NB == 2 ? 6 : 5;             // MFMAs with a weight load behind them
                 static_for<NMF>([&](auto mc) __attribute__((always_inline)) {
                     constexpr int m = decltype(mc)::value;
-                    constexpr int r = m / NJ, j = m % NJ;
+                    constexpr int r = m / NJ, j = (r & 1) ? NJ - 1 - m % NJ : m % NJ;   // back and forth: one operand stays at each row change
                     constexpr bool ld = LB && m >= LB0 && (m - LB0) % LBS == 0 && (m - LB0) / LBS < 2 * NB;
                     if constexpr (ld) mfma_load_b(integral_constant<int, r>{}, integral_constant<int, j>{}, AX[r], BF[HP][j], integral_constant<int, nslot>{}, integral_constant<int, (m - LB0) / LBS>{}, kn);
                     else mfma(integral_constant<int, r>{}, integral_constant<int, j>{}, AX[r], BF[HP][j]);
@@ -435,7 +435,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                 constexpr int NF1 = NJ + RT;                        // fetches of group 1: B0, A0, B1 .. B(NJ-1), A1 .. A(RT-1)
                 static_for<NG>([&](auto mc) __attribute__((always_inline)) {
                     constexpr int m = decltype(mc)::value;
-                    constexpr int r = m / NH, j = NH + m % NH;
+                    constexpr int r = m / NH, j = NH + ((r & 1) ? NH - 1 - m % NH : m % NH);
                     constexpr bool ld = LA && HP == 0 && m >= NG - NA;              // the last NA MFMAs have an activation load behind them
                     const i32x4& a_prev = HP ? AX[r] : AY[r];       // half-step k-1 used the other set
                     if constexpr (ld) mfma_load_a(integral_constant<int, r>{}, integral_constant<int, j>{}, a_prev, BF[HP ^ 1][j], integral_constant<int, ld ? m - (NG - NA) : 0>{});
@@ -454,7 +454,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                 constexpr int LBS = NG / (2 * NB);                  // every LBS-th MFMA has a weight load behind it
                 static_for<NG>([&](auto mc) __attribute__((always_inline)) {
                     constexpr int m = decltype(mc)::value;
-                    constexpr int r = m / NH, j = m % NH;
+                    constexpr int r = m / NH, j = (r & 1) ? NH - 1 - m % NH : m % NH;
                     constexpr bool ld = LB && m % LBS == 0 && m / LBS < 2 * NB;
                     const i32x4& a_cur = HP ? AY[r] : AX[r];
                     if constexpr (ld) mfma_load_b(integral_constant<int, r>{}, integral_constant<int, j>{}, a_cur, BF[HP][j], integral_constant<int, nslot>{}, integral_constant<int, ld ? m / LBS : 0>{}, kn);
