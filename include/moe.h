@@ -123,7 +123,7 @@ typedef struct moe_workspace_layout {
     size_t row_of;     /* int32[R] */
     size_t row_w;      /* float[R]: gate weight of each permuted row */
     size_t scan;       /* scratch of the permutation kernels */
-    size_t x_perm;     /* dtype[R][H] */
+    size_t x_perm;     /* dtype[R][H]; moe_layer leaves it unwritten when the gate/up GEMM gathers the rows itself */
     size_t h;          /* dtype[R][F] */
     size_t out;        /* float[R][H] */
     size_t total;      /* bytes needed by moe_layer */
@@ -171,7 +171,10 @@ int moe_combine(const moe_shape* s, const float* out, const int32_t* row_of,
 
 /* a5. The whole layer in one call, on one stream, without host synchronisation.
  * Intermediates live in `workspace` at the offsets of moe_workspace_layout_get
- * and may be inspected after the stream has finished. */
+ * and may be inspected after the stream has finished.  With bf16 data and option
+ * "fuse_gather" = 1 (the default) the gate/up GEMM reads row r of its input as
+ * x[row_src[r] / k], and x_perm is not written (needs T * H * 2 < 2^32, else the copy
+ * is made). */
 int moe_layer(const moe_shape* s, const void* x, const void* Wr, const float* bias,
               const int32_t* page_table, const void* page_pool, int64_t pool_pages,
               float* y, void* workspace, size_t workspace_bytes, void* stream);

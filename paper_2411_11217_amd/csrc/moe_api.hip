@@ -18,8 +18,9 @@ static int g_opts[OPT_COUNT] = {
     /*OPT_PROFILE*/ 0,       // 1: moe_layer records stage events (see moe_profile_read)
     /*OPT_DOWN_COLS*/ 0,     // column tiles of the bf16 down GEMM: 0 = by grid size, 1 = 128 wide, 2 = 256 wide
     /*OPT_HALF_TILES*/ 1,    // 1: bf16 row tiles with at most 128 rows run the half-height loop
+    /*OPT_FUSE_GATHER*/ 1,   // 1: the bf16 gate/up GEMM of moe_layer reads the rows of x through row_src (no x_perm copy)
 };
-static const char* g_opt_names[OPT_COUNT] = {"xcd_remap", "profile", "down_cols", "half_tiles"};
+static const char* g_opt_names[OPT_COUNT] = {"xcd_remap", "profile", "down_cols", "half_tiles", "fuse_gather"};
 int get_opt(int id) { return g_opts[id]; }
 
 int validate_shape(const moe_shape* s) {
@@ -204,10 +205,14 @@ static int layer_body(const moe_shape& s, const void* x, const void* Wr, const f
     int rc = launch_route(s, x, Wr, bias, ids, w, nullptr, st);
     if (rc != MOE_OK) return rc;
     prof_mark(ps, 1, st);
-    rc = launch_permute(s, ids, w, x, counts, offsets, row_src, row_of, row_w, ws + L.x_perm, ws + L.scan, st);
+    // bf16: the gate/up GEMM gathers the rows of x by itself (32-bit byte offsets into x), and x_perm stays unwritten
+    const bool fuse = s.dtype == MOE_DTYPE_BF16 && get_opt(OPT_FUSE_GATHER) && (int64_t)s.T * s.H * 2 < ((int64_t)1 << 32);
+    rc = launch_permute(s, ids, w, fuse ? nullptr : x, counts, offsets, row_src, row_of, row_w,
+                        fuse ? nullptr : ws + L.x_perm, ws + L.scan, st);
     if (rc != MOE_OK) return rc;
     prof_mark(ps, 2, st);
-    rc = ffn(ws + L.x_perm, offsets, row_w, ws + L.h, (float*)(ws + L.out), status, prof_event(ps, 3));
+    rc = ffn(fuse ? x : ws + L.x_perm, fuse ? row_src : nullptr, offsets, row_w, ws + L.h, (float*)(ws + L.out), status,
+             prof_event(ps, 3));
     if (rc != MOE_OK) return rc;
     prof_mark(ps, 4, st);
     // the gate weight was applied in the down-projection epilogue: plain sum here
@@ -225,10 +230,10 @@ size_t layer_workspace_bytes(const moe_shape& s) {
 int layer_resident(const moe_shape& sh, const void* x, const void* Wr, const float* bias, const int32_t* page_table,
                    const char* page_pool, int64_t pool_pages, float* y, char* workspace, hipStream_t st) {
     return layer_body(sh, x, Wr, bias, y, workspace, st,
-                      [&](const void* xp, const int32_t* offsets, const float* row_w, void* h, float* out,
-                          int32_t* status, hipEvent_t mid) {
+                      [&](const void* xp, const int32_t* gather_src, const int32_t* offsets, const float* row_w, void* h,
+                          float* out, int32_t* status, hipEvent_t mid) {
                           FfnArgs a{xp, offsets, page_table, page_pool, pool_pages, row_w, h, out,
-                                    status, 0, sh.E, 0, mid};
+                                    status, 0, sh.E, 0, mid, gather_src};
                           return launch_expert_ffn(sh, a, st);
                       });
 }
@@ -479,8 +484,8 @@ static int enqueue_expert_copy(moe_streamer* st, int e, hipStream_t copy) {
     return MOE_OK;
 }
 
-static int ffn_streamed(moe_streamer* st, const void* x_perm, const int32_t* offsets, const float* row_w,
-                        void* h_ws, float* out, int32_t* status, hipStream_t comp, hipStream_t copy) {
+static int ffn_streamed(moe_streamer* st, const void* x_perm, const int32_t* gather_src, const int32_t* offsets,
+                        const float* row_w, void* h_ws, float* out, int32_t* status, hipStream_t comp, hipStream_t copy) {
     const moe_shape& s = st->shape;
     const Geom& g = st->geom;
     // the copy stream must not overwrite a slot that GEMMs enqueued earlier on the
@@ -494,7 +499,8 @@ static int ffn_streamed(moe_streamer* st, const void* x_perm, const int32_t* off
         if (rc != MOE_OK) return rc;
         MOE_HIP_TRY(hipEventRecord(st->loaded[sl], copy));
         MOE_HIP_TRY(hipStreamWaitEvent(comp, st->loaded[sl], 0));
-        FfnArgs a{x_perm, offsets, st->slot_table, st->slots, 2 * g.ppe, row_w, h_ws, out, status, e, e + 1, 2, nullptr};
+        FfnArgs a{x_perm, offsets, st->slot_table, st->slots, 2 * g.ppe, row_w, h_ws, out, status, e, e + 1, 2, nullptr,
+                  gather_src};
         rc = launch_expert_ffn(s, a, comp);
         if (rc != MOE_OK) return rc;
         MOE_HIP_TRY(hipEventRecord(st->released[sl], comp));
@@ -512,7 +518,7 @@ int moe_expert_ffn_streamed(moe_streamer* st, const void* x_perm, const int32_t*
     if (!st) return MOE_ERR_INVALID_ARG;
     if (st->shape.T == 0) return MOE_OK;
     if (!x_perm || !offsets || !h_ws || !out || stream == copy_stream) return MOE_ERR_INVALID_ARG;
-    return ffn_streamed(st, x_perm, offsets, row_w, h_ws, out, status, (hipStream_t)stream, (hipStream_t)copy_stream);
+    return ffn_streamed(st, x_perm, nullptr, offsets, row_w, h_ws, out, status, (hipStream_t)stream, (hipStream_t)copy_stream);
 }
 
 int moe_layer_streamed(moe_streamer* st, const void* x, const void* Wr, const float* bias,
@@ -528,9 +534,9 @@ int moe_layer_streamed(moe_streamer* st, const void* x, const void* Wr, const fl
     if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_INVALID_ARG;
     hipStream_t comp = (hipStream_t)stream, copy = (hipStream_t)copy_stream;
     return layer_body(sh, x, Wr, bias, y, (char*)workspace, comp,
-                      [&](const void* xp, const int32_t* offsets, const float* row_w, void* h, float* out,
-                          int32_t* status, hipEvent_t) {
-                          return ffn_streamed(st, xp, offsets, row_w, h, out, status, comp, copy);
+                      [&](const void* xp, const int32_t* gather_src, const int32_t* offsets, const float* row_w, void* h,
+                          float* out, int32_t* status, hipEvent_t) {
+                          return ffn_streamed(st, xp, gather_src, offsets, row_w, h, out, status, comp, copy);
                       });
 }
 

@@ -215,6 +215,15 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     MOE_TL(1);
     const int e = tc.e, nt = tc.nt, row0 = tc.row0, rows_here = tc.rows_here;
 
+    // With a_gather the activation rows come from the matrix at A through an index: lane L of the wavefront
+    // looks up the source of the wavefront's row (L / 8 * 4 + wave) * 8 + L % 8 here (one division per lane,
+    // the load under way during the page-table lookups).
+    uint32_t gathered = 0;
+    if (p.a_gather) {
+        const int r = min(((lane >> 3) * kWaves + wave) * 8 + (lane & 7), rows_here - 1);     // row0 + r is a row of this expert
+        gathered = (uint32_t)min(max(p.a_gather[row0 + r] / p.a_div, 0), p.a_rows - 1);      // clamped into the matrix at A
+    }
+
     // ---- weight tiles through the page table -------------------------------------
     const int32_t* trow = p.table + (size_t)(p.table_row_mod ? e % p.table_row_mod : e) * p.ppe + p.group_base;
     const int pt0 = nt * NB;
@@ -256,15 +265,17 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     // instruction q = i*4 + wave (i = 0..7) fills LDS rows q*8 .. q*8+7 (1 KiB); lane j holds row
     // q*8 + j/8 at chunk position j%8, i.e. global chunk (j%8) ^ ((row >> 1) & 7).  Rows past the
     // tail repeat the last row.
+    // With a_gather the lanes pick the eight sources they load from the ones looked up above.
     uint32_t a_off[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int lrow = (i * kWaves + wave) * 8 + (lane >> 3);
         const int r = min(lrow, rows_here - 1);
         const int c = (lane & 7) ^ ((lrow >> 1) & 7);
-        a_off[i] = (uint32_t)r * (uint32_t)p.lda_bytes + c * 16;
+        const uint32_t src = p.a_gather ? (uint32_t)__shfl((int)gathered, i * 8 + (lane >> 3)) : (uint32_t)r;
+        a_off[i] = src * (uint32_t)p.lda_bytes + c * 16;
     }
-    const char* a_ptr = p.A + (int64_t)row0 * p.lda_bytes;    // + 128 bytes per k-step
+    const char* a_ptr = p.a_gather ? p.A : p.A + (int64_t)row0 * p.lda_bytes;    // + 128 bytes per k-step
     int a_wr = kRingA;                                         // LDS offset of the activation stage being filled
     const uint32_t b_off = wave * 1024 + lane * 16;            // weight half-tiles are copied linearly
 

@@ -31,6 +31,8 @@ struct GemmParams {
     int32_t* status;
     int32_t xcd_remap;
     int32_t half_tiles;       // bf16 kernel: row tiles with at most 128 rows run the half-height loop
+    const int32_t* a_gather;  // bf16 kernel, or null: row r of A is row a_gather[r] / a_div of the matrix at A (a_rows rows)
+    int32_t a_div, a_rows;
 };
 
 struct TileCoord {
@@ -151,6 +153,9 @@ inline void fill_gate_up(GemmParams& p, const moe_shape& s, const Geom& g, const
     p.ldo = s.F;
     p.n_cols = s.F;
     p.row_w = nullptr;
+    p.a_gather = a.gather_src;
+    p.a_div = s.k;
+    p.a_rows = s.T;
 }
 
 inline void fill_down(GemmParams& p, const moe_shape& s, const Geom& g, const FfnArgs& a) {
@@ -164,6 +169,7 @@ inline void fill_down(GemmParams& p, const moe_shape& s, const Geom& g, const Ff
     p.ldo = s.H;
     p.n_cols = s.H;
     p.row_w = a.row_w;
+    p.a_gather = nullptr;
 }
 
 }  // namespace moe

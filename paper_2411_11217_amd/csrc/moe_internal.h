@@ -52,7 +52,7 @@ void set_hip_error(hipError_t e);
     } while (0)
 
 int get_opt(int id);
-enum Opt { OPT_XCD_REMAP = 0, OPT_PROFILE, OPT_DOWN_COLS, OPT_HALF_TILES, OPT_COUNT };
+enum Opt { OPT_XCD_REMAP = 0, OPT_PROFILE, OPT_DOWN_COLS, OPT_HALF_TILES, OPT_FUSE_GATHER, OPT_COUNT };
 
 // ---- kernel launchers (each returns MOE_OK or MOE_ERR_HIP) -----------------
 int launch_route(const moe_shape& s, const void* x, const void* Wr, const float* bias,
@@ -76,6 +76,7 @@ struct FfnArgs {
     int e_begin, e_end;        // experts processed by this launch
     int table_row_mod;         // 0: table row = e; n>0: table row = e % n (streamed slots)
     hipEvent_t mid_event;      // recorded between the gate/up and the down launch when not null
+    const int32_t* gather_src = nullptr;   // bf16 only.  Not null: x_perm is x [T][H], and row r reads x[gather_src[r] / k]
 };
 int launch_expert_ffn(const moe_shape& s, const FfnArgs& a, hipStream_t st);
 int launch_expert_ffn_bf16(const moe_shape& s, const Geom& g, const FfnArgs& a, hipStream_t st);

@@ -144,9 +144,9 @@ def test_reduced_cases_stagewise_and_layer(name, down_cols):
 
 
 @pytest.mark.parametrize("name", ["bf16_top2_of_4", "bf16_two_experts_ragged", "f32_top2_of_5"])
-@pytest.mark.parametrize("option,default", [("xcd_remap", 1)])
+@pytest.mark.parametrize("option,default", [("xcd_remap", 1), ("fuse_gather", 1)])
 def test_tile_numbering_options_give_identical_bits(option, default, name):
-    # which block computes which tile does not change any arithmetic
+    # which block computes which tile, and who gathers the rows of x, does not change any arithmetic
     case = Case(MED[name])
     y1, _ = M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev)
     M.set_option(option, 1 - default)
@@ -256,7 +256,8 @@ def test_streamed_pages_match_resident_pages_bitwise():
             torch.cuda.synchronize()
             assert_status_clean(ws_st.view("status").cpu().tolist())
             assert torch.equal(y_st, y_res)
-        h, out = M.moe_expert_ffn_streamed(st, ws_res.view("x_perm"), ws_res.view("offsets"), row_w=ws_res.view("row_w"))
+        x_perm = res.x[ws_res.view("row_src").long() // cfg.k].contiguous()   # moe_layer gathered inside its GEMM
+        h, out = M.moe_expert_ffn_streamed(st, x_perm, ws_res.view("offsets"), row_w=ws_res.view("row_w"))
         torch.cuda.synchronize()
         assert torch.equal(out, ws_res.view("out")) and torch.equal(h, ws_res.view("h"))
     finally:
