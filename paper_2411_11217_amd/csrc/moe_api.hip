@@ -180,10 +180,6 @@ static void prof_mark(int slot, int j, hipStream_t st) {
 }
 static hipEvent_t prof_event(int slot, int j) { return slot >= 0 ? g_prof.ev[slot][j] : nullptr; }
 
-__global__ void clear_status_kernel(int32_t* status) {
-    if (threadIdx.x < 4) status[threadIdx.x] = 0;
-}
-
 // The body of the layer on one stream; `ffn` runs the expert FFN stage.
 template <class FfnFn>
 static int layer_body(const moe_shape& s, const void* x, const void* Wr, const float* bias, float* y,
@@ -198,8 +194,6 @@ static int layer_body(const moe_shape& s, const void* x, const void* Wr, const f
     int32_t* row_src = (int32_t*)(ws + L.row_src);
     int32_t* row_of = (int32_t*)(ws + L.row_of);
     float* row_w = (float*)(ws + L.row_w);
-    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, st, status);   // a kernel, so the call can be graph-captured
-    MOE_HIP_TRY(hipGetLastError());
     const int ps = prof_slot();
     prof_mark(ps, 0, st);
     int rc = launch_route(s, x, Wr, bias, ids, w, nullptr, st);
@@ -208,7 +202,7 @@ static int layer_body(const moe_shape& s, const void* x, const void* Wr, const f
     // bf16: the gate/up GEMM gathers the rows of x by itself (32-bit byte offsets into x), and x_perm stays unwritten
     const bool fuse = s.dtype == MOE_DTYPE_BF16 && get_opt(OPT_FUSE_GATHER) && (int64_t)s.T * s.H * 2 < ((int64_t)1 << 32);
     rc = launch_permute(s, ids, w, fuse ? nullptr : x, counts, offsets, row_src, row_of, row_w,
-                        fuse ? nullptr : ws + L.x_perm, ws + L.scan, st);
+                        fuse ? nullptr : ws + L.x_perm, ws + L.scan, status, st);   // also clears the status words (in a kernel: the call can be graph-captured)
     if (rc != MOE_OK) return rc;
     prof_mark(ps, 2, st);
     rc = ffn(fuse ? x : ws + L.x_perm, fuse ? row_src : nullptr, offsets, row_w, ws + L.h, (float*)(ws + L.out), status,
@@ -323,7 +317,7 @@ int moe_permute(const moe_shape* s, const int32_t* topk_ids, const float* topk_w
     if (!workspace) return MOE_ERR_INVALID_ARG;
     if (workspace_bytes < permute_workspace_bytes(*s)) return MOE_ERR_WORKSPACE_TOO_SMALL;
     return launch_permute(*s, topk_ids, topk_w, x, counts, offsets, row_src, row_of, row_w, x_perm,
-                          workspace, (hipStream_t)stream);
+                          workspace, nullptr, (hipStream_t)stream);
 }
 
 int moe_expert_ffn(const moe_shape* s, const void* x_perm, const int32_t* offsets,

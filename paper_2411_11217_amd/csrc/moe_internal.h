@@ -61,7 +61,7 @@ int launch_route(const moe_shape& s, const void* x, const void* Wr, const float*
 size_t permute_workspace_bytes(const moe_shape& s);
 int launch_permute(const moe_shape& s, const int32_t* ids, const float* topk_w, const void* x,
                    int32_t* counts, int32_t* offsets, int32_t* row_src, int32_t* row_of,
-                   float* row_w, void* x_perm, void* ws, hipStream_t st);
+                   float* row_w, void* x_perm, void* ws, int32_t* status_to_clear, hipStream_t st);   // status_to_clear: int32[4] zeroed by the index kernels, or null
 
 struct FfnArgs {
     const void* x_perm;        // dtype [R][H]

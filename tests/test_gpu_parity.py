@@ -123,6 +123,23 @@ def test_expert_ffn_row_counts_across_the_tile_variants(down_cols):
         assert_close(out.cpu().numpy()[lo:hi], o_ref[lo:hi], "bf16", f"out, expert {e} with {c} rows")
 
 
+@pytest.mark.parametrize("T,E,k", [(1, 1, 1), (1000, 1, 1), (512, 3, 2), (513, 3, 2), (4096, 8, 2), (16384, 64, 1),
+                                   (5000, 16, 4), (40000, 64, 2), (131072, 8, 2), (140000, 5, 2)])
+def test_permutation_block_counts(T, E, k):
+    # one block (no count kernel), up to 256 blocks (each placing block sums the block counts), more (scan kernel)
+    rng = np.random.default_rng(T + E)
+    skew = rng.random(E) ** 3 + 1e-3                      # some experts rare, some popular
+    ids = np.stack([rng.choice(E, size=k, replace=False, p=skew / skew.sum()) for _ in range(T)]).astype(np.int32)
+    w = rng.random((T, k), dtype=np.float32)
+    ref = oracle.permute(ids, E)
+    s = M.MoEShape(T, 128, 128, E, k, M.DTYPE_BF16, 16384)
+    pm = M.moe_permute(s, _dev_i32(ids), topk_w=_dev_f32(w))
+    torch.cuda.synchronize()
+    for name in ("counts", "offsets", "row_src", "row_of"):
+        assert np.array_equal(pm[name].cpu().numpy(), ref[name]), name
+    assert np.array_equal(pm["row_w"].cpu().numpy(), w.reshape(-1)[ref["row_src"]])
+
+
 def test_c1_stagewise_and_layer():
     case = Case(C1)
     ref = run_stagewise(case)
