@@ -77,9 +77,9 @@ def test_crossover_micro_batch_is_the_ridge():
 
 # (layer, N, mu, r_w, measured ms per layer on one MI355X; bench.py and bench.py --pipeline)
 MEASURED = [
-    (hrm.MIXTRAL_8X7B, 256, 256, 1.0, 0.558, 0.10),
-    (hrm.MIXTRAL_8X7B, 4096, 4096, 1.0, 2.35, 0.10),
-    (hrm.MIXTRAL_8X22B, 8192, 8192, 1.0, 7.75, 0.10),
+    (hrm.MIXTRAL_8X7B, 256, 256, 1.0, 0.53, 0.10),
+    (hrm.MIXTRAL_8X7B, 4096, 4096, 1.0, 2.30, 0.10),
+    (hrm.MIXTRAL_8X22B, 8192, 8192, 1.0, 7.52, 0.10),
     (hrm.DBRX, 16384, 4096, 0.0, 115.3, 0.10),
     (hrm.DBRX, 16384, 4096, 48 / 95, 59.0, 0.10),
     # next to the turning point (link time = GPU time) the copies and the kernels slow each other down
