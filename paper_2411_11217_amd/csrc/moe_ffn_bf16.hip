@@ -170,9 +170,6 @@ __device__ __forceinline__ void static_for(F&& f) {
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-#ifdef MOE_FFN_TIMELINE
-__device__ __forceinline__ long long rows_here_tl(int rows) { return (long long)rows << 8; }
-#endif
 
 // NB: page tiles per block along the columns.  2: the 256-column block described above.  1 (MODE 1
 // only): 256 rows x 128 columns, wavefront tile 128 x 64, for launches with too few 256-wide tiles
@@ -191,13 +188,6 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
 
-#ifdef MOE_FFN_TIMELINE   // experiment builds only: per-block time stamps behind the status words
-    long long* tl = (long long*)(p.status + 4) + ((size_t)blockIdx.x + MODE * 6144) * 8;
-    const long long t_entry = clock64();
-#define MOE_TL(i) do { if (tid == 0) tl[i] = clock64() - t_entry; } while (0)
-#else
-#define MOE_TL(i) ((void)0)
-#endif
     // ---- which tile is mine -------------------------------------------------
     const TileCoord tc = locate_tile<BM>(p);
     if (!tc.valid) return;
@@ -209,10 +199,6 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         probe_c = clock64();
         probe_w = wall_clock64();
     }
-#ifdef MOE_FFN_TIMELINE
-    if (tid == 0) { tl[0] = t_entry; tl[5] = wall_clock64(); tl[7] = 1 + rows_here_tl(tc.rows_here) + ((long long)(__builtin_amdgcn_s_getreg(6164) & 15) << 32); }
-#endif
-    MOE_TL(1);
     const int e = tc.e, nt = tc.nt, row0 = tc.row0, rows_here = tc.rows_here;
 
     // With a_gather the activation rows come from the matrix at A through an index: lane L of the wavefront
@@ -544,7 +530,6 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         }
         mfma_drain();
     };
-    MOE_TL(2);
     // A row tile with at most 128 rows takes the half-height loop; any other whose last rows are missing
     // runs the full loop on repeated rows (skipping single MFMAs would take a branch each: a wavefront
     // issues about one instruction in four clocks, and the branches cost more than the MFMAs they skip).
@@ -558,7 +543,6 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     else main_loop(std::true_type{}, integral_constant<int, 2>{}, integral_constant<int, 1>{});
     const bool wact = !half_tile || wm == 0 || rows_here > 64;        // this wavefront has rows
     const int row_tiles = !half_tile ? 8 : (rows_here > 32 ? 4 : 2);   // and this many row tiles
-    MOE_TL(3);
 
     // ---- epilogue ---------------------------------------------------------------------
     // accumulator register r of lane l in MFMA tile (i, j) is the element at row i*16 + (l/16)*4 + r,
@@ -631,10 +615,6 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
             else store_rows(std::false_type{}, std::integral_constant<int, 8>{});
         }
     }
-    MOE_TL(4);
-#ifdef MOE_FFN_TIMELINE
-    if (tid == 0) tl[6] = wall_clock64() - tl[5];
-#endif
     if (clock_probe) {
         const long long dc = clock64() - probe_c, dw = wall_clock64() - probe_w;
         if (dw > 0) p.status[2 + MODE] = (int32_t)(dc * 100 / dw);       // MHz

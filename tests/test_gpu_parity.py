@@ -123,6 +123,21 @@ def test_expert_ffn_row_counts_across_the_tile_variants(down_cols):
         assert_close(out.cpu().numpy()[lo:hi], o_ref[lo:hi], "bf16", f"out, expert {e} with {c} rows")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("T,H,E,k", [(1, 128, 1, 1), (17, 128, 3, 3), (100, 384, 16, 4), (33, 1024, 17, 2), (250, 256, 32, 8),
+                                     (47, 640, 33, 5), (130, 2048, 64, 64), (2000, 512, 8, 2)])
+def test_router_shapes(T, H, E, k, dtype):
+    # token counts off the 16-token blocks, fewer 64-element units than wavefronts, every expert-padding bound, a bias
+    bias = ((0, 0.5), (E - 1, -0.25)) if E > 1 else ((0, 1.0),)
+    cfg = MoEConfig("route", dtype, T=T, H=H, F=128, E=E, k=k, page_bytes=64 * 1024, seed=40 + E, bias=bias)
+    case = Case(cfg)
+    ref = case.oracle_route()
+    ids, w, logits = M.moe_route(case.shape, case.x, case.Wr, bias=case.bias, want_logits=True)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(logits.cpu().numpy(), ref["logits"], rtol=0, atol=2e-5 * max(1.0, np.abs(ref["logits"]).max()))
+    compare_routing(cfg, ids.cpu().numpy(), w.cpu().numpy(), ref)
+
+
 @pytest.mark.parametrize("T,E,k", [(1, 1, 1), (1000, 1, 1), (512, 3, 2), (513, 3, 2), (4096, 8, 2), (16384, 64, 1),
                                    (5000, 16, 4), (40000, 64, 2), (131072, 8, 2), (140000, 5, 2)])
 def test_permutation_block_counts(T, E, k):
