@@ -147,7 +147,8 @@ def main():
         R, H, F, T, E, b = cfg.R, cfg.H, cfg.F, cfg.T, cfg.E, (2 if cfg.dtype == "bf16" else 4)
         alg_bytes = {   # algorithmic HBM bytes of the copy-like stages
             "route": T * H * b + E * H * b + 8 * R,
-            "permute": T * H * b + R * H * b + 12 * R,
+            # index arrays only when the gate/up GEMM gathers the rows of x itself (bf16, the default)
+            "permute": 12 * R + (0 if cfg.dtype == "bf16" and M.get_option("fuse_gather") else T * H * b + R * H * b),
             "combine": 4 * R * H + 4 * R + 4 * T * H,
         }
         extra = {

@@ -316,7 +316,16 @@ int moe_pre_attention(const moe_linear_shape* qkv_proj, const float* hidden, con
 
 /* ------------------------------------------------------------------ tuning knobs
  * Named integer options for experiments (kernel variants, tile order); unknown
- * names give MOE_ERR_INVALID_ARG.  Defaults are the measured best. */
+ * names give MOE_ERR_INVALID_ARG.  Defaults are the measured best.  No option
+ * changes a result bit.
+ *   "xcd_remap"   1: column-tile groups of the expert GEMMs are dealt round robin to the
+ *                 8 XCDs; 0: block b computes tile b.                       default 1
+ *   "half_tiles"  1: bf16 row tiles with at most 128 rows run shorter loops.   default 1
+ *   "down_cols"   column tiles of the bf16 down GEMM: 0 = by grid size, 1 = 128 wide,
+ *                 2 = 256 wide.                                              default 0
+ *   "fuse_gather" 1: moe_layer's bf16 gate/up GEMM gathers the rows of x itself (no
+ *                 x_perm copy).                                              default 1
+ *   "profile"     1: moe_layer records stage events (see below).             default 0 */
 int moe_set_option(const char* name, int value);
 int moe_get_option(const char* name, int* value);
 
