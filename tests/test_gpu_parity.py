@@ -176,12 +176,13 @@ def test_reduced_cases_stagewise_and_layer(name, down_cols):
 
 
 @pytest.mark.parametrize("name", ["bf16_top2_of_4", "bf16_two_experts_ragged", "f32_top2_of_5"])
-@pytest.mark.parametrize("option,default", [("xcd_remap", 1), ("fuse_gather", 1)])
-def test_tile_numbering_options_give_identical_bits(option, default, name):
-    # which block computes which tile, and who gathers the rows of x, does not change any arithmetic
+@pytest.mark.parametrize("option,default,other", [("xcd_remap", 1, 0), ("fuse_gather", 1, 0), ("half_tiles", 1, 0),
+                                                  ("down_cols", 0, 1), ("down_cols", 0, 2)])
+def test_kernel_options_give_identical_bits(option, default, other, name):
+    # which block computes which tile, the tile variant, and who gathers the rows of x do not change any arithmetic
     case = Case(MED[name])
     y1, _ = M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev)
-    M.set_option(option, 1 - default)
+    M.set_option(option, other)
     try:
         y0, _ = M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev)
     finally:
