@@ -49,6 +49,13 @@ def main():
                     help="instead of the headline step, time the post-attention task (O projection, residual + norm, MoE "
                          "layer) and the pre-attention task (residual + norm, QKV projection) on --config's layer shape, "
                          "with attention width H and a QKV width of 1.5 H (32 query and 8 key/value heads of 128)")
+    ap.add_argument("--prefill", action="store_true",
+                    help="instead of the headline step, time a prefill pass of a request batch through --config's layer "
+                         "(weights resident): --requests seeded prompt lengths (average 77, maximum 418) are packed into "
+                         "micro-batches of --ubs requests by paper_2411_11217_amd.batching, and a step runs moe_layer once "
+                         "per micro-batch on that micro-batch's prompt tokens")
+    ap.add_argument("--requests", type=int, default=1024)
+    ap.add_argument("--ubs", type=int, default=128)
     ap.add_argument("--layers", type=int, default=2)
     ap.add_argument("--micro-batches", type=int, default=4)
     ap.add_argument("--resident-fraction", type=float, default=0.5)
@@ -84,6 +91,8 @@ def main():
         return pipeline_bench(args, cfg, M, make_inputs)
     if args.tasks:
         return tasks_bench(args, cfg, M, make_inputs)
+    if args.prefill:
+        return prefill_bench(args, cfg, M, make_inputs)
     s = M.make_shape(cfg.T, cfg.H, cfg.F, cfg.E, cfg.k, cfg.dtype, cfg.page_bytes)
     t0 = time.time()
     inp = make_inputs(cfg, threads=16)
@@ -247,6 +256,53 @@ def tasks_bench(args, cfg, M, make_inputs):
                       "qkv_projection": round(2.0 * T * H * Nq / ms["qkv_projection"] / 1e9, 1)},
            "add_rmsnorm_gbs": round((2 * T * H * 4 + T * H * 4 + T * H * 2) / ms["add_rmsnorm"] / 1e6, 1)}
     print(json.dumps(out), flush=True)
+
+
+def prefill_bench(args, cfg, M, make_inputs):
+    """A prefill pass: variable-length requests -> balanced micro-batches (the paper's appendix A.2) -> the layer once
+    per micro-batch on its prompt tokens (in prefill the whole layer runs on the GPU, the paper's section 3.2)."""
+    import torch
+    from moe_workloads import prompt_lengths
+    from paper_2411_11217_amd.batching import Request, batch_requests
+    lens = prompt_lengths(args.requests, seed=cfg.seed)
+    n_ub = (args.requests + args.ubs - 1) // args.ubs
+    mbs, aborted = batch_requests([Request(i, int(v)) for i, v in enumerate(lens)], n_ub, args.ubs, gen_len=128,
+                                  cache_size=1 << 40)
+    assert not aborted
+    tokens = [mb.prompt_tokens for mb in mbs]
+    inp = make_inputs(cfg, threads=16)
+    s_max = M.make_shape(max(tokens), cfg.H, cfg.F, cfg.E, cfg.k, cfg.dtype, cfg.page_bytes)
+    pw = M.PagedWeights(s_max, inp["W1"], inp["W3"], inp["W2"])
+    pw.to_device(keep_host=False)
+    Wr = inp["Wr"].cuda()
+    g = torch.Generator().manual_seed(cfg.seed)
+    shapes = [M.make_shape(t, cfg.H, cfg.F, cfg.E, cfg.k, cfg.dtype, cfg.page_bytes) for t in tokens]
+    xs = [torch.randn((t, cfg.H), generator=g).to(cfg.torch_dtype).cuda() for t in tokens]
+    ys = [torch.empty((t, cfg.H), dtype=torch.float32, device="cuda") for t in tokens]
+    wss = [M.Workspace(sh) for sh in shapes]
+
+    def step():
+        for sh, x, y, ws in zip(shapes, xs, ys, wss):
+            M.moe_layer(sh, x, Wr, pw.table_dev, pw.pages_dev, workspace=ws, y=y)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    total = sum(tokens)
+    flops = 6.0 * total * cfg.k * cfg.H * cfg.F
+    print(json.dumps({
+        "metric": "prefill pass of a request batch through one MoE layer, prompt tokens/s", "value": round(total / (ms * 1e-3), 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name + " (layer shape), prefill", "requests": args.requests, "ubs": args.ubs,
+                   "prompt_len_avg": round(float(lens.mean()), 2), "prompt_len_max": int(lens.max()),
+                   "micro_batch_tokens": tokens},
+        "expert_gemms_tflops_lower_bound": round(flops / (ms * 1e-3) / 1e12, 1)}), flush=True)
 
 
 def pipeline_bench(args, cfg, M, make_inputs):

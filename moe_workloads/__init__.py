@@ -145,6 +145,23 @@ def make_inputs(cfg: MoEConfig, threads: int = 8, identical_experts: bool = Fals
     return out
 
 
+def prompt_lengths(n: int, seed: int, s_avg: int = 77, s_max: int = 418, s_min: int = 4) -> np.ndarray:
+    """n seeded prompt lengths standing in for a request mix of which the paper gives the average
+    and the maximum (its table of workload configurations; the defaults are the MTBench row).
+    Log-normal (sigma 0.7: most prompts short, a long tail), clipped to [s_min, s_max], scaled so that
+    the mean comes out at s_avg; the longest request is set to s_max.  The shape of the distribution
+    is this module's choice: the paper prints only the two numbers."""
+    rng = np.random.Generator(np.random.Philox(key=[(seed << 16) ^ 0x4c45, 0]))
+    z = np.exp(0.7 * rng.standard_normal(n))
+    scale = s_avg / z.mean()
+    for _ in range(20):                                   # the clipping moves the mean: a few fixed-point steps
+        lens = np.clip(np.rint(z * scale), s_min, s_max)
+        scale *= s_avg / lens.mean()
+    lens = np.clip(np.rint(z * scale), s_min, s_max).astype(np.int64)
+    lens[int(np.argmax(lens))] = s_max
+    return lens
+
+
 def oracle_view(t: Optional[torch.Tensor]) -> Optional[np.ndarray]:
     """The numpy array the oracle takes for a CPU tensor: float32 as is,
     bfloat16 as its uint16 bit patterns (no copy)."""

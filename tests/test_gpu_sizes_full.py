@@ -12,7 +12,7 @@ import torch
 
 import oracle
 import paper_2411_11217_amd as M
-from moe_workloads import CONFIGS
+from moe_workloads import CONFIGS, prompt_lengths, scaled
 from util import Case, assert_close, assert_h_close, check_permutation_valid, compare_routing, say, assert_status_clean
 
 pytestmark = pytest.mark.gpu
@@ -98,6 +98,24 @@ def test_mixtral_8x7b_t256_with_the_row_copy():
         check_full(case, y, ws, cfg.name + " fuse_gather=0")
     finally:
         M.set_option("fuse_gather", 1)
+
+
+def test_mixtral_8x7b_prefill_micro_batch():
+    # a prefill micro-batch as the request batching forms it from a seeded prompt-length mix (average 77, maximum
+    # 418, 128 requests per micro-batch): a token count that none of the tile sizes divides
+    from paper_2411_11217_amd.batching import Request, batch_requests
+    lens = prompt_lengths(1024, seed=2)
+    mbs, aborted = batch_requests([Request(i, int(v)) for i, v in enumerate(lens)], 8, 128, gen_len=128, cache_size=1 << 40)
+    assert not aborted and len(mbs) == 8
+    tokens = [mb.prompt_tokens for mb in mbs]
+    assert max(tokens) - min(tokens) <= 418 and sum(tokens) == int(lens.sum())
+    T = next(t for t in tokens if t % 256 != 0)
+    cfg = scaled(CONFIGS["c3_mixtral8x7b_t4096"], name="prefill_micro_batch", T=T)
+    say(f"    micro-batch tokens: {tokens}, running T={T}")
+    case = Case(cfg)
+    y, ws = M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev)
+    torch.cuda.synchronize()
+    check_full(case, y, ws, cfg.name)
 
 
 def test_mixtral_8x22b_skewed():
