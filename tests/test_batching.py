@@ -84,3 +84,18 @@ def test_degenerate_inputs():
     a = batch_requests(reqs([4] * 10), 2, 5, 0, 10**9)
     b = batch_requests(reqs([4] * 10), 2, 5, 0, 10**9)
     assert [[r.rid for r in mb.requests] for mb in a[0]] == [[r.rid for r in mb.requests] for mb in b[0]]
+
+
+def test_prompt_length_stand_in_has_the_papers_mean_and_maximum_and_packs_evenly():
+    # the paper's table of workload configurations gives 77 / 418 (MTBench), 242 / 256, 1693 / 1984
+    import numpy as np
+    from moe_workloads import prompt_lengths
+    for s_avg, s_max in ((77, 418), (242, 256), (1693, 1984)):
+        lens = prompt_lengths(1024, seed=5, s_avg=s_avg, s_max=s_max)
+        assert lens.shape == (1024,) and lens.min() >= 4 and lens.max() == s_max
+        assert abs(lens.mean() - s_avg) < 0.01 * s_avg
+        assert np.array_equal(lens, prompt_lengths(1024, seed=5, s_avg=s_avg, s_max=s_max))      # seeded
+        assert not np.array_equal(lens, prompt_lengths(1024, seed=6, s_avg=s_avg, s_max=s_max))
+        mbs, aborted = batch_requests([Request(i, int(v)) for i, v in enumerate(lens)], 8, 128, gen_len=64, cache_size=1 << 40)
+        tokens = [mb.prompt_tokens for mb in mbs]
+        assert not aborted and sum(tokens) == lens.sum() and max(tokens) - min(tokens) <= s_max
