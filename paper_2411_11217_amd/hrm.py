@@ -40,7 +40,7 @@ class Hardware:
 # (expert GEMMs on the 4096-token Mixtral-8x7B-shaped layer, weight streaming on the 256-token
 # one, page copies from pinned host memory).
 MI355X_PEAK = Hardware(p_g=2.5e15, b_g=8.0e12, b_cg=64e9)
-MI355X_MEASURED = Hardware(p_g=1.24e15, b_g=5.5e12, b_cg=55.7e9)
+MI355X_MEASURED = Hardware(p_g=1.26e15, b_g=5.5e12, b_cg=57.0e9)
 
 
 @dataclasses.dataclass(frozen=True)
@@ -105,16 +105,18 @@ def balance_intensity(hw: Hardware, i_gpu: float) -> float:
     return hw.b_g * i_gpu / hw.b_cg
 
 
-def layer_latency(layer: Layer, hw: Hardware, N: int, mu: int, r_w: float) -> Dict[str, float]:
+def layer_latency(layer: Layer, hw: Hardware, N: int, mu: int, r_w: float, hidden_from_host: bool = True) -> Dict[str, float]:
     """Per-layer latency of one pass of N tokens in micro-batches of mu (section 4.2):
-    T = max(comm, T_gpu) with comm = (1 - r_w) * weight bytes / b_cg and
+    T = max(comm, T_gpu), comm = the bytes that go from the host to the GPU for the layer / b_cg, i.e. the
+    non-resident weights (1 - r_w) * weight bytes and, with hidden_from_host, the hidden state of every
+    token (h1 * dt bytes: in the paper's pipeline it comes back from the attention on the host), and
     T_gpu = sum over micro-batches of max(FLOPs / p_g, GPU bytes / b_g)."""
     n_full, rest = divmod(N, mu)
     t_gpu = 0.0
     for tokens, count in ((mu, n_full), (rest, 1 if rest else 0)):
         if count:
             t_gpu += count * max(layer.flops(tokens) / hw.p_g, layer.gpu_bytes(tokens) / hw.b_g)
-    comm = (1.0 - r_w) * layer.weight_bytes / hw.b_cg
+    comm = ((1.0 - r_w) * layer.weight_bytes + (N * layer.h1 * layer.dt if hidden_from_host else 0.0)) / hw.b_cg
     t = max(comm, t_gpu)
     flops = layer.flops(N)
     i_link = flops / ((1.0 - r_w) * layer.weight_bytes) if r_w < 1.0 else math.inf
