@@ -125,6 +125,17 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     tokens_per_s = cfg.T / (ms_per_step * 1e-3)
 
+    # the spread over single steps (events around every step, outside the timed region above)
+    n_ev = min(args.steps, 100)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev + 1)]
+    evs[0].record()
+    for i in range(n_ev):
+        step()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    per_step = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(n_ev))
+    spread = {"n": n_ev, "median": round(per_step[n_ev // 2], 4), "min": round(per_step[0], 4), "max": round(per_step[-1], 4)}
+
     # the same steps again with the library's stage events on (HIP events on the launch stream)
     stages, n_prof = {}, 0
     if streamer is None:
@@ -193,7 +204,7 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "T": cfg.T, "H": cfg.H, "F": cfg.F, "E": cfg.E, "k": cfg.k,
                    "page_bytes": cfg.page_bytes, "weights": "pinned host, streamed" if cfg.streamed else "resident in HBM"},
-        "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "single_step_ms": spread,
     }
     if streamer is not None:
         link_bytes = pw.pages_host.numel() * pw.pages_host.element_size()
