@@ -54,6 +54,10 @@ def main():
                          "(weights resident): --requests seeded prompt lengths (average 77, maximum 418) are packed into "
                          "micro-batches of --ubs requests by paper_2411_11217_amd.batching, and a step runs moe_layer once "
                          "per micro-batch on that micro-batch's prompt tokens")
+    ap.add_argument("--mu-sweep", action="store_true",
+                    help="instead of the headline step, time moe_layer on --config's layer shape (weights resident) for "
+                         "micro-batch sizes 32 .. 4096: the memory-bound plateau of the decode stage (the paper's section "
+                         "6.2 sweeps 32 .. 256) and the turn to compute bound beyond it")
     ap.add_argument("--requests", type=int, default=1024)
     ap.add_argument("--ubs", type=int, default=128)
     ap.add_argument("--layers", type=int, default=2)
@@ -93,6 +97,8 @@ def main():
         return tasks_bench(args, cfg, M, make_inputs)
     if args.prefill:
         return prefill_bench(args, cfg, M, make_inputs)
+    if args.mu_sweep:
+        return mu_sweep_bench(args, cfg, M, make_inputs)
     s = M.make_shape(cfg.T, cfg.H, cfg.F, cfg.E, cfg.k, cfg.dtype, cfg.page_bytes)
     t0 = time.time()
     inp = make_inputs(cfg, threads=16)
@@ -267,6 +273,43 @@ def tasks_bench(args, cfg, M, make_inputs):
                       "qkv_projection": round(2.0 * T * H * Nq / ms["qkv_projection"] / 1e9, 1)},
            "add_rmsnorm_gbs": round((2 * T * H * 4 + T * H * 4 + T * H * 2) / ms["add_rmsnorm"] / 1e6, 1)}
     print(json.dumps(out), flush=True)
+
+
+def mu_sweep_bench(args, cfg, M, make_inputs):
+    """Layer latency against the micro-batch size mu on one layer shape; the model's prediction beside it."""
+    import torch
+    from paper_2411_11217_amd import hrm
+    inp = make_inputs(cfg, threads=16)
+    mus = [32, 64, 128, 256, 512, 1024, 2048, 4096]
+    s_max = M.make_shape(max(mus), cfg.H, cfg.F, cfg.E, cfg.k, cfg.dtype, cfg.page_bytes)
+    pw = M.PagedWeights(s_max, inp["W1"], inp["W3"], inp["W2"])
+    pw.to_device(keep_host=False)
+    Wr = inp["Wr"].cuda()
+    g = torch.Generator().manual_seed(cfg.seed)
+    x_all = torch.randn((max(mus), cfg.H), generator=g).to(cfg.torch_dtype).cuda()
+    layer = hrm.Layer(cfg.H, cfg.F, cfg.E, cfg.k, 2 if cfg.dtype == "bf16" else 4)
+    weight_bytes = 3.0 * cfg.E * cfg.H * cfg.F * (2 if cfg.dtype == "bf16" else 4)
+    rows = []
+    for mu in mus:
+        sh = M.make_shape(mu, cfg.H, cfg.F, cfg.E, cfg.k, cfg.dtype, cfg.page_bytes)
+        x, ws = x_all[:mu].contiguous(), M.Workspace(sh)
+        y = torch.empty((mu, cfg.H), dtype=torch.float32, device="cuda")
+        for _ in range(args.warmup):
+            M.moe_layer(sh, x, Wr, pw.table_dev, pw.pages_dev, workspace=ws, y=y)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            M.moe_layer(sh, x, Wr, pw.table_dev, pw.pages_dev, workspace=ws, y=y)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        model = hrm.layer_latency(layer, hrm.MI355X_MEASURED, mu, mu, 1.0, hidden_from_host=False)
+        rows.append({"mu": mu, "ms": round(ms, 4), "tokens_per_s": round(mu / (ms * 1e-3), 1),
+                     "weight_tb_per_s": round(weight_bytes / (ms * 1e-3) / 1e12, 2),
+                     "tflops": round(6.0 * mu * cfg.k * cfg.H * cfg.F / (ms * 1e-3) / 1e12, 1),
+                     "model_ms": round(model["T"] * 1e3, 4)})
+    print(json.dumps({"metric": "MoE layer latency against the micro-batch size (weights resident)", "unit": "ms",
+                      "steps": args.steps, "warmup": args.warmup, "dtype": cfg.dtype, "data": "synthetic",
+                      "config": {"workload": cfg.name + " (layer shape), micro-batch sweep"}, "sweep": rows}), flush=True)
 
 
 def prefill_bench(args, cfg, M, make_inputs):
