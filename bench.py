@@ -38,6 +38,9 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--option", action="append", default=[], help="library option name=value")
+    ap.add_argument("--shuffle-host-pages", action="store_true",
+                    help="streamed workloads: place the pages in pinned host memory in a random order, so that every "
+                         "page is a copy of its own (in order, the runs of consecutive pages of an expert go out as one copy)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="instead of the layer, run a plain device copy of 1 GiB ten times (calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc against known traffic)")
@@ -102,7 +105,8 @@ def main():
     s = M.make_shape(cfg.T, cfg.H, cfg.F, cfg.E, cfg.k, cfg.dtype, cfg.page_bytes)
     t0 = time.time()
     inp = make_inputs(cfg, threads=16)
-    pw = M.PagedWeights(s, inp["W1"], inp["W3"], inp["W2"], pin=cfg.streamed)
+    order = torch.Generator().manual_seed(1) if (cfg.streamed and args.shuffle_host_pages) else None
+    pw = M.PagedWeights(s, inp["W1"], inp["W3"], inp["W2"], pin=cfg.streamed, order=order)
     x, Wr = inp["x"].cuda(), inp["Wr"].cuda()
     bias = None if inp["bias"] is None else inp["bias"].cuda()
     streamer = None
@@ -215,6 +219,7 @@ def main():
     if streamer is not None:
         link_bytes = pw.pages_host.numel() * pw.pages_host.element_size()
         extra["host_link"] = {"bytes_per_step": link_bytes, "gbs": round(link_bytes / (ms_per_step * 1e-3) / 1e9, 2),
+                              "host_pages": "random order, one copy per page" if args.shuffle_host_pages else "in order, one copy per expert",
                               "note": "every weight page crosses the host link once per step; the step is bound by it"}
     out.update(extra)
     print(json.dumps(out), flush=True)
