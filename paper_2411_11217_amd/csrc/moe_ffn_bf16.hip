@@ -140,6 +140,19 @@ __device__ __forceinline__ void mfma_16x16x32_then_load(const i32x4& a, const i3
                  : "memory", "m0");
 #endif
 }
+// The same MFMA with its accumulator tile in vector registers the compiler allocates, and a plain 16-byte load
+// into vector registers: the tall tiles' extra row tile.  The load is not known to the compiler's wait counting;
+// its result is used only behind a wait that covers it.
+__device__ __forceinline__ void mfma_16x16x32_v(f32x4& acc, const i32x4& a, const i32x4& b) {
+#ifdef __HIP_DEVICE_COMPILE__
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+#endif
+}
+__device__ __forceinline__ void load_vgpr_16(i32x4& dst, const char* ptr) {
+#ifdef __HIP_DEVICE_COMPILE__
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(ptr) : "memory");
+#endif
+}
 template <int R>
 __device__ __forceinline__ void acc_zero() {
 #ifdef __HIP_DEVICE_COMPILE__
@@ -263,6 +276,23 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     }
     const char* a_ptr = p.a_gather ? p.A : p.A + (int64_t)row0 * p.lda_bytes;    // + 128 bytes per k-step
     int a_wr = kRingA;                                         // LDS offset of the activation stage being filled
+    // A tall tile (more than BM rows: the remainder of at most 32 rows of its expert): wavefront row wm also
+    // computes the 16 rows BM + wm*16 .. against its column fragments, which are in registers anyway.  The
+    // activation fragment of those rows comes straight from memory (16 bytes per lane and half-step, four
+    // half-steps ahead), the eight accumulator tiles live in vector registers.
+    const int extra = rows_here > BM ? rows_here - BM : 0;
+    const char* ae_ptr = p.A;
+    i32x4 AE[4];
+    f32x4 accE[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) accE[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < 4; ++u) AE[u] = i32x4{0, 0, 0, 0};
+    if (extra) {
+        const int er = min(BM + wm * 16 + (lane & 15), rows_here - 1);
+        const int64_t src = p.a_gather ? (int64_t)min(max(p.a_gather[row0 + er] / p.a_div, 0), p.a_rows - 1) : (int64_t)row0 + er;
+        ae_ptr = p.A + src * p.lda_bytes + (lane >> 4) * 16;      // + 64 bytes per half-step
+    }
     const uint32_t b_off = wave * 1024 + lane * 16;            // weight half-tiles are copied linearly
 
     // The loads issued during half-step h: activation instructions (h & 1) * 4 + i (i = 0..3) of the
@@ -427,6 +457,13 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                         MOE_FENCE();
                     }
                 });
+                if (__builtin_expect(extra != 0, 0)) {       // tall tile: the extra row tile against the column fragments of k
+#pragma unroll
+                    for (int jj = 0; jj < NJ; ++jj) mfma_16x16x32_v(accE[jj], AE[U], BF[HP][jj]);
+                    MOE_FENCE();
+                    if (k + 4 < KH) load_vgpr_16(AE[U], ae_ptr + (int64_t)(k + 4) * 64);
+                    MOE_FENCE();
+                }
             } else if (wact) {
                 constexpr int NH = NJ / 2, NG = RT * NH;            // column fragments and MFMAs of a group
                 constexpr int NF1 = NJ + RT;                        // fetches of group 1: B0, A0, B1 .. B(NJ-1), A1 .. A(RT-1)
@@ -487,6 +524,10 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         const std::false_type N{};
         // prologue, in the order the half-steps -4 .. -1 would have issued them: activation k-steps
         // 0 and 1, weight half-steps 0 .. 2 (KH is a multiple of 4 and at least 4)
+        if (!HALF && extra) {             // the oldest loads of the tile: complete at the first wait
+#pragma unroll
+            for (int u = 0; u < 4; ++u) load_vgpr_16(AE[u], ae_ptr + u * 64);
+        }
 #pragma unroll
         for (int i = 0; i < (HALF ? NA : 4); ++i) load_a(0, i);
 #pragma unroll
@@ -529,6 +570,8 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
             });
         }
         mfma_drain();
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) asm volatile("" : "+v"(accE[j]));      // read only behind the drain
     };
     // A row tile with at most 128 rows takes the half-height loop; any other whose last rows are missing
     // runs the full loop on repeated rows (skipping single MFMAs would take a branch each: a wavefront
@@ -549,7 +592,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     // column l%16 of that 16 x 16 tile
     const int col_l = lane & 15;
     const int a_row_base = wm * (half_tile ? 64 : 128) + (lane >> 4) * 4;
-    const bool full_rows = rows_here == BM;
+    const bool full_rows = rows_here >= BM;
     // store(i, v): the 4 x NJ x 16 values of row tile i of this wavefront
     auto for_row_tiles = [&](auto n_c, auto&& store) __attribute__((always_inline)) {
         static_for<decltype(n_c)::value>([&](auto ic) __attribute__((always_inline)) {
@@ -582,12 +625,24 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         } else if (row_tiles == 2) store_rows(std::false_type{}, std::integral_constant<int, 2>{});
         else if (row_tiles == 4) store_rows(std::false_type{}, std::integral_constant<int, 4>{});
         else store_rows(std::false_type{}, std::integral_constant<int, 8>{});
+        if (extra) {                           // the extra row tile of a tall tile
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = BM + wm * 16 + (lane >> 4) * 4 + r;
+                if (row < rows_here) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        h[(int64_t)row * p.ldo + j * 16] = (__bf16)silu_mul(accE[j][r], accE[j + 4][r]);
+                }
+            }
+        }
     } else {
         // the 256 row weights of the tile go through LDS (free now): one load per thread instead of
         // one dependent global load per accumulator row
         float* sw = (float*)smem;
         __syncthreads();                       // every wavefront has left the main loop
         sw[tid] = (p.row_w && tid < rows_here) ? p.row_w[row0 + tid] : 1.0f;
+        if (tid < 32) sw[BM + tid] = (p.row_w && BM + tid < rows_here) ? p.row_w[row0 + BM + tid] : 1.0f;     // a tall tile's extra rows
         __syncthreads();
         const int d0 = nt * (128 * NB) + wn * (16 * NJ);   // n_cols is a multiple of 128: with NB = 2 a wavefront's columns are all valid or all not
         if (d0 < p.n_cols) {
@@ -613,6 +668,17 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
             } else if (row_tiles == 2) store_rows(std::false_type{}, std::integral_constant<int, 2>{});
             else if (row_tiles == 4) store_rows(std::false_type{}, std::integral_constant<int, 4>{});
             else store_rows(std::false_type{}, std::integral_constant<int, 8>{});
+            if (extra) {                       // the extra row tile of a tall tile
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = BM + wm * 16 + (lane >> 4) * 4 + r;
+                    if (row < rows_here) {
+                        const float wr = sw[row];
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) o[(int64_t)row * p.ldo + j * 16] = accE[j][r] * wr;
+                    }
+                }
+            }
         }
     }
     if (clock_probe) {
@@ -689,6 +755,7 @@ int launch_linear_bf16(const LinearArgs& a, hipStream_t st) {
     p.status = a.status;
     p.xcd_remap = get_opt(OPT_XCD_REMAP);
     p.half_tiles = get_opt(OPT_HALF_TILES);
+    p.tall_rows = get_opt(OPT_TALL_TILES) ? 32 : 0;
     const int wide_tiles = (p.n_page_tiles + 1) / 2;
     if ((int64_t)(a.T / BM + 1) * wide_tiles < 2 * kComputeUnits) {       // too few 256-wide tiles to fill the chip
         p.NT = p.n_page_tiles;

@@ -33,6 +33,7 @@ struct GemmParams {
     int32_t half_tiles;       // bf16 kernel: row tiles with at most 128 rows run the half-height loop
     const int32_t* a_gather;  // bf16 kernel, or null: row r of A is row a_gather[r] / a_div of the matrix at A (a_rows rows)
     int32_t a_div, a_rows;
+    int32_t tall_rows;        // bf16 kernel: the last row tile of an expert takes up to this many rows beyond BM (0 or 32)
 };
 
 struct TileCoord {
@@ -81,7 +82,8 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     // groups of mine below group number n: ceil((n - x) / stride) for n >= 0 (0 <= x < stride)
     const int g_lo = lane * p.NT, g_hi = g_lo + p.NT;              // group numbers of my lane's expert
     const int c_lo = (g_lo - x + stride - 1) / stride, c_hi = (g_hi - x + stride - 1) / stride;
-    const int mtiles_l = (cnt + BM - 1) / BM;                        // row tiles of my lane's expert
+    // row tiles of my lane's expert; a remainder of at most tall_rows rows rides on the tile before it
+    const int mtiles_l = cnt > 0 ? max(1, (cnt - p.tall_rows + BM - 1) / BM) : 0;
     const int tiles_l = (c_hi - c_lo) * mtiles_l;
     const int incl = lane_prefix_sum(tiles_l, lane);
     if (idx >= __builtin_amdgcn_readlane(incl, 63)) return t;
@@ -98,7 +100,7 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     t.nt = x + (first + j) * stride - src * p.NT;
     t.mt = rem - j * mtiles;
     t.row0 = seg + t.mt * BM;
-    t.rows_here = min(BM, rows - t.mt * BM);
+    t.rows_here = t.mt == mtiles - 1 ? rows - t.mt * BM : BM;      // the last one may have up to BM + tall_rows
     t.valid = t.rows_here > 0;
     return t;
 }
@@ -138,6 +140,7 @@ inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const 
     p.status = a.status;
     p.xcd_remap = get_opt(OPT_XCD_REMAP);
     p.half_tiles = get_opt(OPT_HALF_TILES);
+    p.tall_rows = (s.dtype == MOE_DTYPE_BF16 && get_opt(OPT_TALL_TILES)) ? 32 : 0;
 }
 
 // parameters of the gate/up launch (K = H, output h[R][F]) and of the down launch

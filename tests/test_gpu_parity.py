@@ -98,8 +98,9 @@ def run_layer(case: Case, ref=None):
 @pytest.mark.parametrize("down_cols", [0, 2])
 def test_expert_ffn_row_counts_across_the_tile_variants(down_cols):
     """Segments of 1 .. 300 rows, one per expert, on both sides of every threshold of the bf16 kernel's row-tile
-    variants (32, 64, 128, 192 rows and the 256-row tile boundary) and an empty one, against the oracle row by row."""
-    counts = [1, 16, 17, 32, 33, 0, 64, 65, 127, 128, 129, 160, 192, 193, 255, 256, 257, 300, 31, 449]
+    variants (32, 64, 128, 192 rows, the 256-row tile boundary, tiles that take a remainder of up to 32 rows along) and an
+    empty one, against the oracle row by row; with the tall tiles switched off every bit stays the same."""
+    counts = [1, 16, 17, 32, 33, 0, 64, 65, 127, 128, 129, 160, 192, 193, 255, 256, 257, 300, 31, 449, 272, 273, 288, 289, 532, 800]
     E, H, F = len(counts), 256, 384
     cfg = MoEConfig("rows", "bf16", T=sum(counts), H=H, F=F, E=E, k=1, page_bytes=64 * 1024, seed=77)
     case = Case(cfg, shuffle_pages=True, extra_pages=1)
@@ -115,6 +116,15 @@ def test_expert_ffn_row_counts_across_the_tile_variants(down_cols):
     finally:
         M.set_option("down_cols", 0)
     assert_status_clean(status.cpu().tolist())
+    M.set_option("down_cols", down_cols)
+    M.set_option("tall_tiles", 0)
+    try:
+        h0, out0 = M.moe_expert_ffn(case.shape, case.x, _dev_i32(offsets), case.pw.table_dev, case.pw.pages_dev, status=status)
+        torch.cuda.synchronize()
+    finally:
+        M.set_option("down_cols", 0)
+        M.set_option("tall_tiles", 1)
+    assert torch.equal(h0, h) and torch.equal(out0, out)
     for e, c in enumerate(counts):
         if c == 0:
             continue
@@ -176,7 +186,7 @@ def test_reduced_cases_stagewise_and_layer(name, down_cols):
 
 
 @pytest.mark.parametrize("name", ["bf16_top2_of_4", "bf16_two_experts_ragged", "f32_top2_of_5"])
-@pytest.mark.parametrize("option,default,other", [("xcd_remap", 1, 0), ("fuse_gather", 1, 0), ("half_tiles", 1, 0),
+@pytest.mark.parametrize("option,default,other", [("xcd_remap", 1, 0), ("fuse_gather", 1, 0), ("half_tiles", 1, 0), ("tall_tiles", 1, 0),
                                                   ("down_cols", 0, 1), ("down_cols", 0, 2)])
 def test_kernel_options_give_identical_bits(option, default, other, name):
     # which block computes which tile, the tile variant, and who gathers the rows of x do not change any arithmetic
