@@ -79,7 +79,7 @@ def test_crossover_micro_batch_is_the_ridge():
 
 
 # (layer, N, mu, r_w, hidden states cross the link, measured ms per layer on one MI355X, tolerance):
-# bench.py (inputs resident) and bench.py --pipeline (hidden states copied from the host), see the design doc
+# bench.py (inputs resident) and bench.py --pipeline (hidden states copied from the host)
 MEASURED = [
     (hrm.MIXTRAL_8X7B, 256, 256, 1.0, False, 0.53, 0.05),
     (hrm.MIXTRAL_8X7B, 4096, 4096, 1.0, False, 2.24, 0.05),
