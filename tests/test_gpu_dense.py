@@ -28,6 +28,8 @@ def paged_linear(ls, W, extra=3, seed=0):
 @pytest.mark.parametrize("T,K,N,page", [
     (300, 256, 384, 3 * 16384),        # ragged rows, odd number of 128-wide column tiles, tiles not dividing pages evenly
     (64, 128, 128, 16384),             # smallest shape: one column tile, 4 half-steps
+    (270, 256, 256, 16384),            # one tall row tile: the 14 rows behind the first 256 ride along
+    (800, 512, 384, 2 * 16384),        # three full row tiles, the last one with 32 more rows
     (1000, 1024, 2048, 1 << 20),       # several row and column tiles
     (4096, 4096, 4096, 2 << 20),       # the O projection of the Mixtral-8x7B shape: 256-wide column tiles
 ])
