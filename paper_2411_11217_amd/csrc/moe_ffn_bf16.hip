@@ -714,13 +714,16 @@ int launch_expert_ffn_bf16(const moe_shape& s, const Geom& g, const FfnArgs& a, 
     if (rc != MOE_OK) return rc;
     if (a.mid_event) MOE_HIP_TRY(hipEventRecord(a.mid_event, st));
     fill_down(p, s, g, a);
-    // Down projection with few row tiles: when even the upper bound of the 256-wide tiles (the routing
-    // result is not known here, R / BM + experts bounds the row tiles) leaves compute units without a
-    // block, the columns are cut into 128-wide tiles instead.  Measured on the Mixtral-8x7B shape: 512
-    // tokens 0.21 against 0.27 ms, 1024 tokens (bound = 256 tiles) 0.43 against 0.33 ms.
+    // Down projection with few row tiles: 256-wide column tiles would leave compute units without a block,
+    // so the columns are cut into 128-wide tiles instead.  The routing result is not known here; the choice
+    // goes by the row tiles an even split of the rows over the experts would give (the grid is sized by the
+    // upper bound as ever).  Measured on the Mixtral-8x7B shape, narrow against wide: 768 tokens 0.23 / 0.29
+    // ms, 1024 tokens 0.26 / 0.32, 1280 tokens 0.45 / 0.38, 2048 tokens 0.48 / 0.38.
     // down_cols: 0 = this rule, 1 / 2 = force NB.
     const int opt = get_opt(OPT_DOWN_COLS);
-    const bool narrow = opt == 1 || (opt == 0 && (int64_t)(R / BM + n_exp) * p.NT < kComputeUnits);
+    const int64_t rows_each = R / s.E;
+    const int64_t row_tiles_each = std::max<int64_t>(1, (rows_each - p.tall_rows + BM - 1) / BM);
+    const bool narrow = opt == 1 || (opt == 0 && n_exp * row_tiles_each * p.NT < kComputeUnits);
     if (narrow) {
         p.NT = (int32_t)g.dt;
         return launch_stages<1, 1>(p, gemm_grid(p.NT, R, BM, n_exp), st);
