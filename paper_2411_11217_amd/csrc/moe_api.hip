@@ -19,7 +19,7 @@ static int g_opts[OPT_COUNT] = {
     /*OPT_DOWN_COLS*/ 0,     // column tiles of the bf16 down GEMM: 0 = by grid size, 1 = 128 wide, 2 = 256 wide
     /*OPT_HALF_TILES*/ 1,    // 1: bf16 row tiles with at most 128 rows run the half-height loop
     /*OPT_FUSE_GATHER*/ 1,   // 1: the bf16 gate/up GEMM of moe_layer reads the rows of x through row_src (no x_perm copy)
-    /*OPT_TALL_TILES*/ 1,    // 1: bf16: a remainder of at most 32 rows behind an expert's last full row tile is computed by that tile's block
+    /*OPT_TALL_TILES*/ 1,    // 1: bf16: row tiles may be up to 32 rows higher than 256 (a small remainder needs no tile of its own)
 };
 static const char* g_opt_names[OPT_COUNT] = {"xcd_remap", "profile", "down_cols", "half_tiles", "fuse_gather", "tall_tiles"};
 int get_opt(int id) { return g_opts[id]; }

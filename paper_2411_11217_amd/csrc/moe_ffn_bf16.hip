@@ -276,7 +276,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     }
     const char* a_ptr = p.a_gather ? p.A : p.A + (int64_t)row0 * p.lda_bytes;    // + 128 bytes per k-step
     int a_wr = kRingA;                                         // LDS offset of the activation stage being filled
-    // A tall tile (more than BM rows: the remainder of at most 32 rows of its expert): wavefront row wm also
+    // A tall tile (up to 32 rows more than BM: its share of the remainder of its expert's rows): wavefront row wm also
     // computes the 16 rows BM + wm*16 .. against its column fragments, which are in registers anyway.  The
     // activation fragment of those rows comes straight from memory (16 bytes per lane and half-step, four
     // half-steps ahead), the eight accumulator tiles live in vector registers.

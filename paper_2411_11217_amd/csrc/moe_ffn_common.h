@@ -33,7 +33,7 @@ struct GemmParams {
     int32_t half_tiles;       // bf16 kernel: row tiles with at most 128 rows run the half-height loop
     const int32_t* a_gather;  // bf16 kernel, or null: row r of A is row a_gather[r] / a_div of the matrix at A (a_rows rows)
     int32_t a_div, a_rows;
-    int32_t tall_rows;        // bf16 kernel: the last row tile of an expert takes up to this many rows beyond BM (0 or 32)
+    int32_t tall_rows;        // bf16 kernel: a row tile may be up to this many rows higher than BM (0 or 32), see locate_tile
 };
 
 struct TileCoord {
@@ -82,8 +82,10 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     // groups of mine below group number n: ceil((n - x) / stride) for n >= 0 (0 <= x < stride)
     const int g_lo = lane * p.NT, g_hi = g_lo + p.NT;              // group numbers of my lane's expert
     const int c_lo = (g_lo - x + stride - 1) / stride, c_hi = (g_hi - x + stride - 1) / stride;
-    // row tiles of my lane's expert; a remainder of at most tall_rows rows rides on the tile before it
-    const int mtiles_l = cnt > 0 ? max(1, (cnt - p.tall_rows + BM - 1) / BM) : 0;
+    // row tiles of my lane's expert.  q full tiles and a remainder r: when r <= tall_rows * q the remainder is
+    // spread over the q tiles (each at most BM + tall_rows rows high), otherwise it is a tile of its own
+    const int q_l = cnt / BM, r_l = cnt - q_l * BM;
+    const int mtiles_l = (q_l >= 1 && r_l <= p.tall_rows * q_l) ? q_l : q_l + (r_l > 0);
     const int tiles_l = (c_hi - c_lo) * mtiles_l;
     const int incl = lane_prefix_sum(tiles_l, lane);
     if (idx >= __builtin_amdgcn_readlane(incl, 63)) return t;
@@ -99,8 +101,15 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     t.e = p.e_begin + src;
     t.nt = x + (first + j) * stride - src * p.NT;
     t.mt = rem - j * mtiles;
-    t.row0 = seg + t.mt * BM;
-    t.rows_here = t.mt == mtiles - 1 ? rows - t.mt * BM : BM;      // the last one may have up to BM + tall_rows
+    const int q = rows / BM, r = rows - q * BM;
+    if (q >= 1 && r <= p.tall_rows * q) {      // q tiles of BM + r / q rows, the first r % q of them one row more
+        const int base = BM + r / q, more = r - (r / q) * q;
+        t.row0 = seg + t.mt * base + min(t.mt, more);
+        t.rows_here = base + (t.mt < more);
+    } else {
+        t.row0 = seg + t.mt * BM;
+        t.rows_here = min(BM, rows - t.mt * BM);
+    }
     t.valid = t.rows_here > 0;
     return t;
 }

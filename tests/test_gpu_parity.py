@@ -100,7 +100,8 @@ def test_expert_ffn_row_counts_across_the_tile_variants(down_cols):
     """Segments of 1 .. 300 rows, one per expert, on both sides of every threshold of the bf16 kernel's row-tile
     variants (32, 64, 128, 192 rows, the 256-row tile boundary, tiles that take a remainder of up to 32 rows along) and an
     empty one, against the oracle row by row; with the tall tiles switched off every bit stays the same."""
-    counts = [1, 16, 17, 32, 33, 0, 64, 65, 127, 128, 129, 160, 192, 193, 255, 256, 257, 300, 31, 449, 272, 273, 288, 289, 532, 800]
+    counts = [1, 16, 17, 32, 33, 0, 64, 65, 127, 128, 129, 160, 192, 193, 255, 256, 257, 300, 31, 449, 272, 273, 288, 289, 532,
+              544, 576, 577, 800, 863, 865, 1061]
     E, H, F = len(counts), 256, 384
     cfg = MoEConfig("rows", "bf16", T=sum(counts), H=H, F=F, E=E, k=1, page_bytes=64 * 1024, seed=77)
     case = Case(cfg, shuffle_pages=True, extra_pages=1)
