@@ -83,7 +83,9 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     const int g_lo = lane * p.NT, g_hi = g_lo + p.NT;              // group numbers of my lane's expert
     const int c_lo = (g_lo - x + stride - 1) / stride, c_hi = (g_hi - x + stride - 1) / stride;
     // row tiles of my lane's expert.  q full tiles and a remainder r: when r <= tall_rows * q the remainder is
-    // spread over the q tiles (each at most BM + tall_rows rows high), otherwise it is a tile of its own
+    // spread over the last ceil(r / tall_rows) of the q tiles (each at most BM + tall_rows rows high: as few
+    // tall tiles as possible, every one costs an extra 16-row MFMA tile per wavefront), otherwise it is a tile
+    // of its own
     const int q_l = cnt / BM, r_l = cnt - q_l * BM;
     const int mtiles_l = (q_l >= 1 && r_l <= p.tall_rows * q_l) ? q_l : q_l + (r_l > 0);
     const int tiles_l = (c_hi - c_lo) * mtiles_l;
@@ -102,10 +104,18 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     t.nt = x + (first + j) * stride - src * p.NT;
     t.mt = rem - j * mtiles;
     const int q = rows / BM, r = rows - q * BM;
-    if (q >= 1 && r <= p.tall_rows * q) {      // q tiles of BM + r / q rows, the first r % q of them one row more
-        const int base = BM + r / q, more = r - (r / q) * q;
-        t.row0 = seg + t.mt * base + min(t.mt, more);
-        t.rows_here = base + (t.mt < more);
+    if (r > 0 && q >= 1 && r <= p.tall_rows * q) {
+        // the last m tiles are BM + r / m rows high, the first r % m of them one row more
+        const int m = (r + p.tall_rows - 1) / p.tall_rows, plain = q - m;
+        const int i = t.mt - plain;
+        if (i < 0) {
+            t.row0 = seg + t.mt * BM;
+            t.rows_here = BM;
+        } else {
+            const int base = BM + r / m, more = r - (r / m) * m;
+            t.row0 = seg + plain * BM + i * base + min(i, more);
+            t.rows_here = base + (i < more);
+        }
     } else {
         t.row0 = seg + t.mt * BM;
         t.rows_here = min(BM, rows - t.mt * BM);
