@@ -26,7 +26,7 @@ PEAK_CLOCK_MHZ = 2400.0       # the clock the published peaks are quoted at
 
 # HBM traffic per launch of the gate/up GEMM on the default workload, in bytes, from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/ (None: not measured).
-MEASURED_TRAFFIC = {"c3_mixtral8x7b_t4096": 5.427e9}
+MEASURED_TRAFFIC = {"c3_mixtral8x7b_t4096": 5.454e9}
 
 
 def main():

@@ -83,7 +83,7 @@ def test_crossover_micro_batch_is_the_ridge():
 MEASURED = [
     (hrm.MIXTRAL_8X7B, 256, 256, 1.0, False, 0.53, 0.05),
     (hrm.MIXTRAL_8X7B, 4096, 4096, 1.0, False, 2.24, 0.05),
-    (hrm.MIXTRAL_8X22B, 8192, 8192, 1.0, False, 7.52, 0.08),
+    (hrm.MIXTRAL_8X22B, 8192, 8192, 1.0, False, 7.48, 0.08),
     (hrm.DBRX, 16384, 4096, 0.0, True, 115.3, 0.03),
     (hrm.DBRX, 16384, 4096, 48 / 95, True, 59.0, 0.03),
     (hrm.DBRX, 16384, 4096, 76 / 95, True, 26.2, 0.03),     # next to the turning point: link time = 1.25 x GPU time
