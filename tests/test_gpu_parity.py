@@ -201,6 +201,24 @@ def test_kernel_options_give_identical_bits(option, default, other, name):
     assert torch.equal(y0, y1)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_shapes_and_routings_against_the_oracle(seed):
+    # seeded random layer shapes with a random router bias (uneven segments of every length up to a few row tiles)
+    rng = np.random.default_rng(1000 + seed)
+    E = int(rng.integers(1, 13))
+    k = int(rng.integers(1, min(E, 4) + 1))
+    T = int(rng.integers(1, 1400))
+    H = int(rng.choice([128, 256, 384]))
+    F = int(rng.choice([128, 256, 640]))
+    bias = tuple((e, float(rng.normal(0.0, 0.35))) for e in range(E)) if E > 1 else ()
+    cfg = MoEConfig(f"rand{seed}", "bf16", T=T, H=H, F=F, E=E, k=k, page_bytes=int(rng.choice([16384, 49152, 65536])),
+                    seed=50 + seed, bias=bias)
+    say(f"    T={T} H={H} F={F} E={E} k={k} page={cfg.page_bytes}")
+    case = Case(cfg, shuffle_pages=bool(seed & 1), extra_pages=seed % 3)
+    y, ws = run_layer(case)
+    say(f"    counts: {ws.view('counts').cpu().tolist()}")
+
+
 def test_page_indirection_is_invisible():
     """Shuffling the physical page slots (table updated with them) leaves every bit of the output unchanged."""
     cfg = MED["bf16_top2_of_4"]
