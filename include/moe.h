@@ -316,8 +316,9 @@ int moe_pre_attention(const moe_linear_shape* qkv_proj, const float* hidden, con
 
 /* ------------------------------------------------------------------ tuning knobs
  * Named integer options for experiments (kernel variants, tile order); unknown
- * names give MOE_ERR_INVALID_ARG.  Defaults are the measured best.  No option
- * changes a result bit.
+ * names give MOE_ERR_INVALID_ARG.  The options are process-wide and read at launch
+ * time without locking: set them before other threads enqueue work.  Defaults are the
+ * measured best.  No option changes a result bit.
  *   "xcd_remap"   1: column-tile groups of the expert GEMMs are dealt round robin to the
  *                 8 XCDs; 0: block b computes tile b.                       default 1
  *   "half_tiles"  1: bf16 row tiles with at most 128 rows run shorter loops.   default 1
