@@ -95,7 +95,7 @@ def run_layer(case: Case, ref=None):
     return y, ws
 
 
-@pytest.mark.parametrize("down_cols", [0, 2])
+@pytest.mark.parametrize("down_cols", [0, 1, 2])
 def test_expert_ffn_row_counts_across_the_tile_variants(down_cols):
     """Segments of 1 .. 300 rows, one per expert, on both sides of every threshold of the bf16 kernel's row-tile
     variants (32, 64, 128, 192 rows, the 256-row tile boundary, tiles that take a remainder of up to 32 rows along) and an
