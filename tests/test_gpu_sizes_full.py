@@ -1,9 +1,12 @@
 """GPU parity at the full workload sizes, in the launch configuration the
-benchmark times (the fused moe_layer call).  The oracle cannot run these sizes
-in full, so: routing and permutation are compared in full (they are cheap), the
-expert FFN and the output on sampled tokens the oracle computes one by one
-(random tokens, the ragged tail rows of every expert, rows of the starved
-expert), plus properties that hold at any size."""
+benchmark times (the fused moe_layer call).  Routing and permutation are compared
+in full (they are cheap).  The expert FFN and the output are compared with the
+oracle in full on the 256-token workload, and on the larger ones on at least 1024
+tokens taken at a stride over the micro-batch plus the rows that make sure every
+(expert, row tile) pair is covered: the first and the last row of every row
+tile, of a tall row tile also the first of its rows beyond 256, and every row of
+an expert with fewer than 256 rows.  Outputs and intermediates are filled with NaN before the call, so a tile
+that was never written cannot pass as stale finite data."""
 import time
 
 import numpy as np
@@ -17,18 +20,84 @@ from util import Case, assert_close, assert_h_close, check_permutation_valid, co
 
 pytestmark = pytest.mark.gpu
 
+ROW_TILE, TALL = 256, 32
 
-def sample_tokens(cfg, ref_pm, ids, n_random=12, seed=0):
-    rng = np.random.default_rng(seed)
-    toks = set(rng.choice(cfg.T, size=min(n_random, cfg.T), replace=False).tolist())
-    toks.update([0, cfg.T - 1])
-    row_src, offsets = ref_pm["row_src"], ref_pm["offsets"]
-    for e in range(cfg.E):
+
+def row_tiles(n):
+    """(first row, rows) of the row tiles the expert GEMMs cut a segment of n rows into, as include/moe.h documents it
+    for the option "tall_tiles": q full tiles of 256 rows and a remainder r; when 0 < r <= 32 q the remainder rides along
+    with the last ceil(r / 32) tiles (each 256 + r / m rows high, the first r % m of them one more), otherwise it is a
+    tile of its own.  Only used to aim the sample, never to compute a value."""
+    q, r = divmod(n, ROW_TILE)
+    if not M.get_option("tall_tiles") or q == 0 or r == 0 or r > TALL * q:
+        return [(a, min(ROW_TILE, n - a)) for a in range(0, n, ROW_TILE)]
+    m = (r + TALL - 1) // TALL
+    base, more = ROW_TILE + r // m, r % m
+    tiles = [(i * ROW_TILE, ROW_TILE) for i in range(q - m)]
+    a = (q - m) * ROW_TILE
+    for i in range(m):
+        rows = base + (1 if i < more else 0)
+        tiles.append((a, rows))
+        a += rows
+    assert a == n
+    return tiles
+
+
+def sample_rows_of_tiles(ref_pm, E):
+    """For every (expert, row tile): its first and last row, and of a tall tile also the first row beyond 256.
+    An expert with fewer than 256 rows gives all its rows.  -> (rows, set of (expert, tile index, part))"""
+    offsets = ref_pm["offsets"]
+    rows, wanted = [], set()
+    for e in range(E):
+        lo, n = int(offsets[e]), int(offsets[e + 1]) - int(offsets[e])
+        if 0 < n < ROW_TILE:
+            rows.extend(range(lo, lo + n))
+        for i, (a, cnt) in enumerate(row_tiles(n)):
+            rows.extend([lo + a, lo + a + cnt - 1])
+            wanted.add((e, i, "body"))
+            if cnt > ROW_TILE:
+                rows.extend([lo + a + ROW_TILE, lo + a + cnt - 1])
+                wanted.add((e, i, "extra rows"))
+    return np.array(sorted(set(rows)), dtype=np.int64), wanted
+
+
+def covered_tiles(rows, ref_pm, E):
+    """The (expert, tile index, part) triples that the compared rows fall into."""
+    offsets = ref_pm["offsets"]
+    got = set()
+    for e in range(E):
         lo, hi = int(offsets[e]), int(offsets[e + 1])
-        if hi > lo:
-            toks.add(int(row_src[hi - 1]) // cfg.k)      # last row of the expert: inside the ragged tail tile
-            toks.add(int(row_src[lo]) // cfg.k)          # first row of the expert
+        mine = rows[(rows >= lo) & (rows < hi)] - lo
+        for i, (a, cnt) in enumerate(row_tiles(hi - lo)):
+            inside = mine[(mine >= a) & (mine < a + cnt)] - a
+            if (inside < ROW_TILE).any():
+                got.add((e, i, "body"))
+            if (inside >= ROW_TILE).any():
+                got.add((e, i, "extra rows"))
+    return got
+
+
+def sample_tokens(cfg, ref_pm, min_tokens=1024):
+    """Token indices to compare: all of them up to min_tokens; beyond, a stride over T giving at least min_tokens, plus
+    the tokens behind the rows of sample_rows_of_tiles."""
+    T, k = cfg.T, cfg.k
+    if T <= min_tokens:
+        return np.arange(T, dtype=np.int32)
+    toks = set(range(0, T, max(1, T // min_tokens)))
+    toks.add(T - 1)
+    rows, _ = sample_rows_of_tiles(ref_pm, cfg.E)
+    toks.update((ref_pm["row_src"][rows] // k).tolist())
     return np.array(sorted(toks), dtype=np.int32)
+
+
+def nan_filled_outputs(case: Case):
+    """A workspace whose intermediates h and out, and an output y, all hold NaN."""
+    cfg = case.cfg
+    ws = M.Workspace(case.shape)
+    ws.view("h").fill_(float("nan"))
+    ws.view("out").fill_(float("nan"))
+    y = torch.full((cfg.T, cfg.H), float("nan"), dtype=torch.float32, device="cuda")
+    return ws, y
 
 
 def check_full(case: Case, y: torch.Tensor, ws, label: str):
@@ -47,15 +116,24 @@ def check_full(case: Case, y: torch.Tensor, ws, label: str):
     say(f"    counts: {pm_gpu['counts'].tolist()}")
     assert pm_gpu["counts"].sum() == cfg.T * cfg.k
     assert_status_clean(ws.view("status").cpu().tolist())
+    # every element of the output and of both intermediates was written (they held NaN before the call)
+    assert not bool(torch.isnan(y).any()), label + ": y has elements the layer never wrote"
+    assert not bool(torch.isnan(ws.view("out")).any()), label + ": out has rows the down GEMM never wrote"
+    assert not bool(torch.isnan(ws.view("h")).any()), label + ": h has elements the gate/up GEMM never wrote"
     yh = y.cpu().numpy()
     assert np.isfinite(yh).all()
 
-    toks = sample_tokens(cfg, pm_ref, ids)
+    toks = sample_tokens(cfg, pm_ref)
+    n_sampled = len(toks)
     toks = toks[same[toks]]                                # near-tie tokens are reported above, not compared
     t0 = time.time()
     v = case.view
     flat = (toks[:, None].astype(np.int64) * cfg.k + np.arange(cfg.k)[None, :]).reshape(-1)
     rows = pm_ref["row_of"][flat]
+    # coverage of the sample: every (expert, row tile) pair has a compared row, a tall tile also among its extra rows
+    _, wanted = sample_rows_of_tiles(pm_ref, cfg.E)
+    missing = wanted - covered_tiles(rows, pm_ref, cfg.E)
+    assert len(missing) <= 2 * int((~same).sum()), sorted(missing)[:5]      # only a near-tie token may take a tile's row away
     xp = oracle.gather_rows(v["x"], pm_ref["row_src"], cfg.k, cfg.dtype_code)
     h_ref, o_ref = oracle.expert_ffn(xp, pm_ref["offsets"], v["W1"], v["W3"], v["W2"], cfg.dtype_code, sel=rows)
     # gate weights of the sampled tokens in the GPU's slot order (same expert set as the oracle's)
@@ -64,7 +142,8 @@ def check_full(case: Case, y: torch.Tensor, ws, label: str):
         lookup = {int(e): rt["w"][t, s] for s, e in enumerate(rt["ids"][t])}
         w_ref[i] = [lookup[int(e)] for e in ids[t]]
     y_ref = oracle.combine(o_ref, np.arange(rows.shape[0], dtype=np.int32), cfg.k, w=w_ref)
-    say(f"    oracle FFN on {len(toks)} sampled tokens ({rows.shape[0]} rows): {time.time() - t0:.1f}s")
+    say(f"    oracle FFN on {len(toks)} of {n_sampled} sampled tokens ({rows.shape[0]} rows covering {len(wanted)} (expert, row tile) "
+        f"parts): {time.time() - t0:.1f}s")
     rows_t = torch.from_numpy(rows.astype(np.int64)).cuda()
     if not M.get_option("fuse_gather"):                    # else the gate/up GEMM gathers the rows, and h below covers them
         assert_close(ws.view("x_perm")[rows_t].float().cpu().numpy(),
@@ -82,7 +161,8 @@ def test_mixtral_8x7b_shapes(name):
     t0 = time.time()
     case = Case(cfg)
     say(f"    inputs + pages ready: {time.time() - t0:.1f}s")
-    y, ws = M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev)
+    ws, y = nan_filled_outputs(case)
+    M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev, workspace=ws, y=y)
     torch.cuda.synchronize()
     check_full(case, y, ws, name)
 
@@ -93,7 +173,8 @@ def test_mixtral_8x7b_t256_with_the_row_copy():
     case = Case(cfg)
     M.set_option("fuse_gather", 0)
     try:
-        y, ws = M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev)
+        ws, y = nan_filled_outputs(case)
+        M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev, workspace=ws, y=y)
         torch.cuda.synchronize()
         check_full(case, y, ws, cfg.name + " fuse_gather=0")
     finally:
@@ -113,7 +194,8 @@ def test_mixtral_8x7b_prefill_micro_batch():
     cfg = scaled(CONFIGS["c3_mixtral8x7b_t4096"], name="prefill_micro_batch", T=T)
     say(f"    micro-batch tokens: {tokens}, running T={T}")
     case = Case(cfg)
-    y, ws = M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev)
+    ws, y = nan_filled_outputs(case)
+    M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev, workspace=ws, y=y)
     torch.cuda.synchronize()
     check_full(case, y, ws, cfg.name)
 
@@ -123,7 +205,8 @@ def test_mixtral_8x22b_skewed():
     t0 = time.time()
     case = Case(cfg)
     say(f"    inputs + pages ready: {time.time() - t0:.1f}s")
-    y, ws = M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev, bias=case.bias)
+    ws, y = nan_filled_outputs(case)
+    M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev, bias=case.bias, workspace=ws, y=y)
     torch.cuda.synchronize()
     share = ws.view("counts").cpu().numpy() / float(cfg.R)
     assert 0.38 <= share[0] <= 0.42 and 0 < share[7] < 0.02, share
@@ -137,7 +220,8 @@ def test_dbrx_streamed_from_pinned_host():
     say(f"    inputs + pinned pages ready: {time.time() - t0:.1f}s")
     st = M.Streamer(case.shape, case.pw.pages_host, case.pw.table_host)
     try:
-        y, ws = M.moe_layer_streamed(st, case.x, case.Wr)
+        ws, y = nan_filled_outputs(case)
+        M.moe_layer_streamed(st, case.x, case.Wr, workspace=ws, y=y)
         torch.cuda.synchronize()
         check_full(case, y, ws, cfg.name)
         # the same layer with every page resident gives the same bits
