@@ -158,7 +158,10 @@ int moe_permute(const moe_shape* s, const int32_t* topk_ids, const float* topk_w
  * and out[r] *= row_w[r] when row_w != NULL.  x_perm: device dtype[R][H];
  * offsets: device int32[E+1]; page_table: device int32[E][pages_per_expert];
  * page_pool: device, pool_pages * page_bytes; h_ws: device dtype[R][F];
- * out: device float[R][H]; status: device int32[4] or NULL (see moe_workspace_layout.status). */
+ * out: device float[R][H]; status: device int32[4] or NULL (see moe_workspace_layout.status).
+ * The kernels only ever OR error bits into status[0] and overwrite status[2], status[3];
+ * they never clear: the CALLER zeroes the four words before the call (moe_layer does that
+ * for its own status words, in one of its kernels). */
 int moe_expert_ffn(const moe_shape* s, const void* x_perm, const int32_t* offsets,
                    const int32_t* page_table, const void* page_pool, int64_t pool_pages,
                    const float* row_w, void* h_ws, float* out, int32_t* status, void* stream);
@@ -206,8 +209,8 @@ int moe_layer_streamed(moe_streamer* st, const void* x, const void* Wr, const fl
 
 /* ------------------------------------------------------------------ weight paging over several layers
  *
- * The I/O side of the paper's pipeline (section 4.1, "Weights Paging and Data
- * Transfer Scheduling", and Algorithm 1; double-buffered weight region of
+ * The I/O side of the paper's pipeline (section 4.1, its paragraph on paging the
+ * weights and scheduling the transfers, and Algorithm 1; double-buffered weight region of
  * appendix A.1; resident fraction r_w of section 4.2) for a stack of n_layers
  * MoE layers of one shape and n micro-batches of shape.T tokens per layer:
  *   - the first resident_pages_per_expert logical pages of every expert of every
@@ -254,9 +257,9 @@ int moe_pipeline_run(moe_pipeline* p, int32_t n_micro, const void* const* x_host
 
 /* ------------------------------------------------------------------ the dense neighbours of the layer
  *
- * The paper's GPU tasks around the MoE FFN (section 4.1): the post-attention task is
- * "primarily O projection and MoE FFN", the pre-attention task "mainly layer norm and
- * QKV projection" of the next micro-batch.  The paper does not write their arithmetic
+ * The paper's GPU tasks around the MoE FFN (section 4.1): the post-attention task (the O
+ * projection, then the MoE FFN) and the pre-attention task (layer norm, then the QKV
+ * projection) of the next micro-batch.  The paper does not write their arithmetic
  * down; the forms are those of the models it evaluates: bias-free linear maps, RMS
  * normalisation with a learned scale, an f32 residual stream.  bf16 only.
  *
@@ -328,7 +331,9 @@ int moe_pre_attention(const moe_linear_shape* qkv_proj, const float* hidden, con
  *                 remainder of an expert's rows needs no tile of its own.        default 1
  *   "fuse_gather" 1: moe_layer's bf16 gate/up GEMM gathers the rows of x itself (no
  *                 x_perm copy).                                              default 1
- *   "profile"     1: moe_layer records stage events (see below).             default 0 */
+ *   "profile"     1: moe_layer records stage events (see below).  Setting it to 1 creates
+ *                 the events (the only option whose setter touches the device; it may
+ *                 return MOE_ERR_HIP); the layer calls themselves create nothing.  default 0 */
 int moe_set_option(const char* name, int value);
 int moe_get_option(const char* name, int* value);
 

@@ -1,8 +1,8 @@
 """CPU oracle for the dense neighbours of the MoE layer -- TEST INFRASTRUCTURE ONLY.
 
-The paper's GPU tasks around the MoE FFN (its section 4.1): the post-attention task is
-"primarily O projection and MoE FFN", the pre-attention task "mainly layer norm and QKV
-projection".  The paper does not write their arithmetic down; the forms below are those of
+The paper's GPU tasks around the MoE FFN (its section 4.1): the post-attention task (the O
+projection, then the MoE FFN) and the pre-attention task (layer norm, then the QKV
+projection).  The paper does not write their arithmetic down; the forms below are those of
 the models it evaluates (a bias-free linear map, RMS normalisation with a learned scale, a
 residual stream), written out in float64 with numpy:
 

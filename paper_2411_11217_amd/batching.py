@@ -16,6 +16,7 @@ reading, since otherwise requests would be lost without being reported as aborte
 from __future__ import annotations
 
 import dataclasses
+import heapq
 from typing import List, Sequence, Tuple
 
 
@@ -40,29 +41,52 @@ class MicroBatch:
         return len(self.requests)
 
 
+class _OpenBatch:
+    """A micro-batch that still takes requests.  It keeps its own running totals and answers the two
+    questions of appendix A.2 itself: would one more request overflow the cache, and is it full."""
+
+    __slots__ = ("slot", "tokens", "members")
+
+    def __init__(self, slot: int):
+        self.slot, self.tokens, self.members = slot, 0, []
+
+    def load(self) -> Tuple[int, int]:
+        return (self.tokens, self.slot)                    # lightest first, the older slot on a tie
+
+    def cache_after(self, req: Request, gen_len: int) -> int:
+        """KV-cache entries at the end of generation if req joined: all prompts plus gen_len per request."""
+        return self.tokens + req.input_len + (len(self.members) + 1) * gen_len
+
+    def add(self, req: Request) -> None:
+        self.members.append(req)
+        self.tokens += req.input_len
+
+    def full(self, ubs: int) -> bool:
+        return len(self.members) >= ubs
+
+
 def batch_requests(requests: Sequence[Request], n_ub: int, ubs: int, gen_len: int,
                    cache_size: int) -> Tuple[List[MicroBatch], List[Request]]:
     """-> (micro_batches, aborted).  n_ub micro-batches of at most ubs requests each."""
     if n_ub < 1 or ubs < 1 or gen_len < 0 or cache_size < 0:
         raise ValueError("n_ub, ubs >= 1 and gen_len, cache_size >= 0 are required")
-    open_batches: List[List[Request]] = [[] for _ in range(n_ub)]
-    open_tokens: List[int] = [0] * n_ub
-    done: List[MicroBatch] = []
+    heap = [(b.load(), b) for b in map(_OpenBatch, range(n_ub))]      # already a valid heap: all loads (0, slot)
+    closed: List[_OpenBatch] = []
     aborted: List[Request] = []
-    # longest first; equal lengths keep their arrival order (stable sort)
-    for req in sorted(requests, key=lambda r: -r.input_len):
-        if not open_batches:
+    by_length = sorted(requests, key=lambda r: r.input_len, reverse=True)   # stable: equal lengths keep arrival order
+    for pos, req in enumerate(by_length):
+        if not heap:                                       # every micro-batch is closed: the rest waits for the next batch
+            aborted.extend(by_length[pos:])
+            break
+        lightest = heap[0][1]
+        if lightest.cache_after(req, gen_len) > cache_size:
             aborted.append(req)
             continue
-        idx = min(range(len(open_batches)), key=lambda i: (open_tokens[i], i))
-        need = open_tokens[idx] + req.input_len + (len(open_batches[idx]) + 1) * gen_len
-        if need > cache_size:
-            aborted.append(req)
-            continue
-        open_batches[idx].append(req)
-        open_tokens[idx] += req.input_len
-        if len(open_batches[idx]) == ubs:
-            done.append(MicroBatch(open_batches.pop(idx)))
-            open_tokens.pop(idx)
-    done.extend(MicroBatch(b) for b in open_batches if b)
-    return done, aborted
+        lightest.add(req)
+        if lightest.full(ubs):
+            heapq.heappop(heap)
+            closed.append(lightest)
+        else:
+            heapq.heapreplace(heap, (lightest.load(), lightest))
+    still_open = sorted((b for _, b in heap if b.members), key=lambda b: b.slot)
+    return [MicroBatch(b.members) for b in closed + still_open], aborted

@@ -20,8 +20,10 @@ static int g_opts[OPT_COUNT] = {
     /*OPT_HALF_TILES*/ 1,    // 1: bf16 row tiles with at most 128 rows run the half-height loop
     /*OPT_FUSE_GATHER*/ 1,   // 1: the bf16 gate/up GEMM of moe_layer reads the rows of x through row_src (no x_perm copy)
     /*OPT_TALL_TILES*/ 1,    // 1: bf16: row tiles may be up to 32 rows higher than 256 (a small remainder needs no tile of its own)
+    /*OPT_STAGGER_NS*/ 0,    // bf16 expert GEMMs: the first block of every compute unit starts this many ns x its stagger unit late
+    /*OPT_STAGGER_MODE*/ 0,  // stagger unit: 0 = row tile index, 1 = position among the 32 blocks of the XCD, 2 = column tile group
 };
-static const char* g_opt_names[OPT_COUNT] = {"xcd_remap", "profile", "down_cols", "half_tiles", "fuse_gather", "tall_tiles"};
+static const char* g_opt_names[OPT_COUNT] = {"xcd_remap", "profile", "down_cols", "half_tiles", "fuse_gather", "tall_tiles", "stagger_ns", "stagger_mode"};
 int get_opt(int id) { return g_opts[id]; }
 
 int validate_shape(const moe_shape* s) {
@@ -163,14 +165,25 @@ struct Profiler {
 };
 static Profiler g_prof;
 
+// Creates the ring of stage events once (called from moe_set_option("profile", 1): the hot calls never create any).
+static int prof_prepare() {
+    if (g_prof.ready) return MOE_OK;
+    for (int i = 0; i < MOE_PROFILE_RING; ++i)
+        for (int j = 0; j <= MOE_PROFILE_STAGES; ++j) {
+            const hipError_t e = hipEventCreate(&g_prof.ev[i][j]);
+            if (e != hipSuccess) {                  // give back what was created
+                for (int q = 0; q < i * (MOE_PROFILE_STAGES + 1) + j; ++q)
+                    (void)hipEventDestroy(g_prof.ev[q / (MOE_PROFILE_STAGES + 1)][q % (MOE_PROFILE_STAGES + 1)]);
+                set_hip_error(e);
+                return MOE_ERR_HIP;
+            }
+        }
+    g_prof.ready = true;
+    return MOE_OK;
+}
+
 static int prof_slot() {
-    if (!g_opts[OPT_PROFILE]) return -1;
-    if (!g_prof.ready) {
-        for (int i = 0; i < MOE_PROFILE_RING; ++i)
-            for (int j = 0; j <= MOE_PROFILE_STAGES; ++j)
-                if (hipEventCreate(&g_prof.ev[i][j]) != hipSuccess) return -1;
-        g_prof.ready = true;
-    }
+    if (!g_opts[OPT_PROFILE] || !g_prof.ready) return -1;
     const int slot = g_prof.next;
     g_prof.next = (g_prof.next + 1) % MOE_PROFILE_RING;
     if (g_prof.count < MOE_PROFILE_RING) ++g_prof.count;
@@ -361,6 +374,10 @@ int moe_set_option(const char* name, int value) {
     if (!name) return MOE_ERR_INVALID_ARG;
     for (int i = 0; i < OPT_COUNT; ++i)
         if (std::strcmp(name, g_opt_names[i]) == 0) {
+            if (i == OPT_PROFILE && value) {        // the stage events are created here, not inside a layer call
+                const int rc = prof_prepare();
+                if (rc != MOE_OK) return rc;
+            }
             g_opts[i] = value;
             return MOE_OK;
         }
@@ -437,11 +454,17 @@ int moe_stream_create(const moe_shape* s, const void* host_pages, int64_t host_p
     st->host_table.assign(host_page_table, host_page_table + (int64_t)s->E * g.ppe);
     st->slots = (char*)slots;
     st->slot_table = slot_table;
-    for (int i = 0; i < 2; ++i) {
-        MOE_HIP_TRY(hipEventCreateWithFlags(&st->loaded[i], hipEventDisableTiming));
-        MOE_HIP_TRY(hipEventCreateWithFlags(&st->released[i], hipEventDisableTiming));
+    // the five events; on a failure those already created are destroyed and the record is freed
+    hipEvent_t* evs[5] = {&st->loaded[0], &st->loaded[1], &st->released[0], &st->released[1], &st->ready};
+    for (int i = 0; i < 5; ++i) {
+        const hipError_t e = hipEventCreateWithFlags(evs[i], hipEventDisableTiming);
+        if (e != hipSuccess) {
+            for (int q = 0; q < i; ++q) (void)hipEventDestroy(*evs[q]);
+            delete st;
+            set_hip_error(e);
+            return MOE_ERR_HIP;
+        }
     }
-    MOE_HIP_TRY(hipEventCreateWithFlags(&st->ready, hipEventDisableTiming));
     *out = st;
     return MOE_OK;
 }

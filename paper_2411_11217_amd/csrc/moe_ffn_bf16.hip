@@ -71,6 +71,13 @@ namespace {
 
 #define MOE_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+#ifdef MOE_TIMELINE      // experimental builds only: per block, wall-clock stamps (100 MHz) at the start, every 16 k-steps and at the end
+__device__ long long g_timeline[2 * 8192 * 24];
+#define MOE_TL_STAMP() do { if (tid == 0 && tli < 23) tl[tli++] = wall_clock64(); } while (0)
+#else
+#define MOE_TL_STAMP() do { } while (0)
+#endif
+
 typedef int i32x4 __attribute__((ext_vector_type(4)));        // an MFMA operand: 8 bf16 in four registers
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) const void* gptr_t;
@@ -213,6 +220,17 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         probe_w = wall_clock64();
     }
     const int e = tc.e, nt = tc.nt, row0 = tc.row0, rows_here = tc.rows_here;
+#ifdef MOE_TIMELINE
+    long long* tl = g_timeline + ((size_t)MODE * 8192 + (blockIdx.x & 8191)) * 24;
+    int tli = 1;
+    if (tid == 0) tl[0] = ((long long)e << 40) | ((long long)tc.mt << 24) | (long long)nt;
+    MOE_TL_STAMP();
+#endif
+    if (p.stagger_ticks > 0 && (blockIdx.x >> 3) < 32) {       // the first block of a compute unit
+        const int unit = p.stagger_mode == 0 ? (tc.mt & 3) : p.stagger_mode == 1 ? (int)((blockIdx.x >> 3) & 31) : (int)(((blockIdx.x >> 3) >> 2) & 7);
+        const long long until = wall_clock64() + (long long)unit * p.stagger_ticks;
+        for (int spin = 0; spin < 100000 && wall_clock64() < until; ++spin) __builtin_amdgcn_s_sleep(4);
+    }
 
     // With a_gather the activation rows come from the matrix at A through an index: lane L of the wavefront
     // looks up the source of the wavefront's row (L / 8 * 4 + wave) * 8 + L % 8 here (one division per lane,
@@ -545,6 +563,9 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         static_for<32 * NJ>([&](auto rc) __attribute__((always_inline)) { acc_zero<decltype(rc)::value>(); });
         int k = 0;
         for (; k + S < KH; k += S) {
+#ifdef MOE_TIMELINE
+            if ((k & 31) == 0) MOE_TL_STAMP();
+#endif
             half_step(k, integral_constant<int, 0>{}, L, L, integral_constant<int, kL2>{});
             half_step(k + 1, integral_constant<int, 1>{}, L, L, integral_constant<int, kL2>{});
             half_step(k + 2, integral_constant<int, 2>{}, L, L, integral_constant<int, kL2>{});
@@ -681,6 +702,10 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
             }
         }
     }
+#ifdef MOE_TIMELINE
+    MOE_TL_STAMP();
+    if (tid == 0) tl[23] = tli;
+#endif
     if (clock_probe) {
         const long long dc = clock64() - probe_c, dw = wall_clock64() - probe_w;
         if (dw > 0) p.status[2 + MODE] = (int32_t)(dc * 100 / dw);       // MHz
@@ -703,6 +728,18 @@ int launch_stages(const GemmParams& p, int grid, hipStream_t st) {
 }
 
 }  // namespace
+
+#ifdef MOE_TIMELINE
+extern "C" int moe_debug_timeline_read(void* dst, size_t bytes) {
+    return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_timeline), bytes < sizeof(g_timeline) ? bytes : sizeof(g_timeline));
+}
+extern "C" int moe_debug_timeline_clear() {
+    void* ptr = nullptr;
+    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_timeline));
+    if (e != hipSuccess) return (int)e;
+    return (int)hipMemset(ptr, 0, sizeof(g_timeline));
+}
+#endif
 
 int launch_expert_ffn_bf16(const moe_shape& s, const Geom& g, const FfnArgs& a, hipStream_t st) {
     const int R = s.T * s.k;

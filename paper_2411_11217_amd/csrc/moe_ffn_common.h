@@ -34,6 +34,8 @@ struct GemmParams {
     const int32_t* a_gather;  // bf16 kernel, or null: row r of A is row a_gather[r] / a_div of the matrix at A (a_rows rows)
     int32_t a_div, a_rows;
     int32_t tall_rows;        // bf16 kernel: a row tile may be up to this many rows higher than BM (0 or 32), see locate_tile
+    int32_t stagger_ticks;    // bf16 kernel: start delay unit of a compute unit's first block, in ticks of the 100 MHz counter
+    int32_t stagger_mode;
 };
 
 struct TileCoord {
@@ -160,6 +162,8 @@ inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const 
     p.xcd_remap = get_opt(OPT_XCD_REMAP);
     p.half_tiles = get_opt(OPT_HALF_TILES);
     p.tall_rows = (s.dtype == MOE_DTYPE_BF16 && get_opt(OPT_TALL_TILES)) ? 32 : 0;
+    p.stagger_ticks = get_opt(OPT_STAGGER_NS) / 10;
+    p.stagger_mode = get_opt(OPT_STAGGER_MODE);
 }
 
 // parameters of the gate/up launch (K = H, output h[R][F]) and of the down launch

@@ -1,5 +1,5 @@
 // Weight paging over a stack of MoE layers: the I/O side of the paper's pipeline
-// (section 4.1, "Weights Paging and Data Transfer Scheduling", and Algorithm 1; the
+// (section 4.1, its paragraph on paging the weights and scheduling the transfers, and Algorithm 1; the
 // double-buffered weight region of appendix A.1; the resident fraction r_w of
 // section 4.2).  Host code only: it orders copies and layer calls on two streams.
 //

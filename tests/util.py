@@ -54,7 +54,7 @@ def assert_h_close(got, ref, dtype: str, what: str):
     """The SwiGLU product h is a ROUNDED intermediate (storage type dt).  The GPU forms it from
     float32 accumulators, the oracle from doubles, so a value that sits near a rounding boundary
     may land on the neighbouring representable number: allow one unit in the last place of the
-    storage type on a small share of elements, plus 1e-4 absolute for values near zero (where
+    storage type on fewer than 5 in a thousand elements (observed: about 6 in ten thousand), plus 1e-4 absolute for values near zero (where
     the float32 accumulation error of g and u, ~1e-5, exceeds the spacing of the type), and hold
     the whole array to the relative-RMS bound."""
     got = np.asarray(got, dtype=np.float64)
@@ -68,7 +68,7 @@ def assert_h_close(got, ref, dtype: str, what: str):
     say(f"    {what}: unequal share={flips:.2e} max|err|={float(diff.max()):.3e} rel-rms={rr:.3e}")
     if dtype == "bf16":
         assert (diff <= 1.001 * ulp + 1e-4).all(), what + ": more than one ulp off"
-        assert flips < 0.02, what + ": too many elements differ"
+        assert flips < 5e-3, what + ": too many elements differ"
         assert rr <= BF16_REL_RMS
     else:
         assert rr <= F32_REL_RMS, what
