@@ -207,6 +207,23 @@ int moe_layer_streamed(moe_streamer* st, const void* x, const void* Wr, const fl
                        float* y, void* workspace, size_t workspace_bytes,
                        void* stream, void* copy_stream);
 
+/* moe_layer for callers that cannot allocate device memory and have no workspace to hand
+ * over (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * the same layer, same kernels and same result bits as moe_layer, with the workspace in a
+ * device array that is part of the library itself (MOE_STATIC_SCRATCH_BYTES per GPU the
+ * library runs on, held until the process ends).  The call allocates and frees nothing.
+ * Shapes whose moe_workspace_layout.total exceeds MOE_STATIC_SCRATCH_BYTES are refused with
+ * MOE_ERR_WORKSPACE_TOO_SMALL before anything is enqueued (the Mixtral-8x7B-shaped layer
+ * fits up to 256 tokens, a decode micro-batch).  The first call on a device looks the
+ * array's address up (no allocation; make that call outside a graph capture).  All calls on
+ * one GPU share that GPU's array: it keeps the last call's intermediates, the status words
+ * are cleared by the layer's kernels at each call, and two calls that overlap in time on
+ * one GPU (different streams) race.  The intermediates are not exposed. */
+#define MOE_STATIC_SCRATCH_BYTES (32u << 20)
+int moe_layer_static(const moe_shape* s, const void* x, const void* Wr, const float* bias,
+                     const int32_t* page_table, const void* page_pool, int64_t pool_pages,
+                     float* y, void* stream);
+
 /* ------------------------------------------------------------------ weight paging over several layers
  *
  * The I/O side of the paper's pipeline (section 4.1, its paragraph on paging the

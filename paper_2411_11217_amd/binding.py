@@ -70,6 +70,7 @@ _SIGNATURES = {
     "moe_expert_ffn": (ctypes.c_int, [_vp] * 5 + [_i64] + [_vp] * 5),
     "moe_combine": (ctypes.c_int, [_vp] * 6),
     "moe_layer": (ctypes.c_int, [_vp] * 6 + [_i64, _vp, _vp, _sz, _vp]),
+    "moe_layer_static": (ctypes.c_int, [_vp] * 6 + [_i64, _vp, _vp]),
     "moe_stream_create": (ctypes.c_int, [_vp, _vp, _i64, _vp, _vp, _vp, _vp]),
     "moe_stream_destroy": (ctypes.c_int, [_vp]),
     "moe_expert_ffn_streamed": (ctypes.c_int, [_vp] * 9),
@@ -350,6 +351,26 @@ def moe_layer(s: MoEShape, x, Wr, page_table, page_pool, bias=None, workspace: O
     _check(_lib().moe_layer(ctypes.byref(s), px, pw, pb, pt, pp, int(page_pool.shape[0]), y.data_ptr(),
                             workspace.buf.data_ptr(), workspace.buf.numel(), _stream(stream)), "moe_layer")
     return y, workspace
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def moe_layer_static(s: MoEShape, x, Wr, page_table, page_pool, y: torch.Tensor, bias=None, stream=None):
+    """moe_layer on the library's own device scratch: nothing is allocated, y is the caller's float32 [T,H]."""
+    gu, d = pages_required(s)
+    dt = s.torch_dtype
+    px = _dev(x, dt, (s.T, s.H), "x")
+    pw = _dev(Wr, dt, (s.E, s.H), "Wr")
+    pb = _dev(bias, torch.float32, (s.E,), "bias")
+    pt = _dev(page_table, torch.int32, (s.E, gu + d), "page_table")
+    pp = _dev(page_pool, torch.uint8, None, "page_pool")
+    if page_pool.dim() != 2 or page_pool.shape[1] != s.page_bytes:
+        raise ValueError("page_pool: expected uint8 [pool_pages, page_bytes]")
+    py = _dev(y, torch.float32, (s.T, s.H), "y")
+    _check(_lib().moe_layer_static(ctypes.byref(s), px, pw, pb, pt, pp, int(page_pool.shape[0]), py, _stream(stream)),
+           "moe_layer_static")
+    return y
 
 
 # ----------------------------------------------------------------------------- streamed pages

@@ -370,6 +370,48 @@ int moe_layer(const moe_shape* s, const void* x, const void* Wr, const float* bi
                           (hipStream_t)stream);
 }
 
+}  // extern "C"
+
+// ---- the layer on the library's own scratch ----------------------------------------------
+// The workspace of moe_layer_static: a file-scope device array, one copy per GPU the library runs on, held until
+// the process ends.  In host code the array's name is only a stand-in; its device address is asked for once
+// per device and kept in g_static_scratch[].
+static __device__ __align__(256) char g_scratch_array[MOE_STATIC_SCRATCH_BYTES];
+static constexpr int kMaxDevices = 64;
+static char* g_static_scratch[kMaxDevices] = {};
+
+// -> MOE_OK and *ptr = the device address of the current device's copy of the array
+static int static_scratch(char** ptr) {
+    int dev = -1;
+    MOE_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return MOE_ERR_INVALID_ARG;
+    if (!g_static_scratch[dev]) {
+        void* p = nullptr;
+        MOE_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(g_scratch_array)));
+        if (!p || ((uintptr_t)p & 255) != 0) return MOE_ERR_INVALID_ARG;
+        g_static_scratch[dev] = (char*)p;
+    }
+    *ptr = g_static_scratch[dev];
+    return MOE_OK;
+}
+
+extern "C" {
+
+int moe_layer_static(const moe_shape* s, const void* x, const void* Wr, const float* bias,
+                     const int32_t* page_table, const void* page_pool, int64_t pool_pages,
+                     float* y, void* stream) {
+    int rc = validate_shape(s);
+    if (rc != MOE_OK) return rc;
+    if (s->T == 0) return MOE_OK;
+    if (!x || !Wr || !page_table || !page_pool || !y || pool_pages <= 0) return MOE_ERR_INVALID_ARG;
+    if (layer_workspace_bytes(*s) > (size_t)MOE_STATIC_SCRATCH_BYTES) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    char* ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc != MOE_OK) return rc;
+    // everything that must start at zero (the status words) is cleared by the layer's own kernels
+    return layer_resident(*s, x, Wr, bias, page_table, (const char*)page_pool, pool_pages, y, ws, (hipStream_t)stream);
+}
+
 int moe_set_option(const char* name, int value) {
     if (!name) return MOE_ERR_INVALID_ARG;
     for (int i = 0; i < OPT_COUNT; ++i)
