@@ -139,12 +139,25 @@ __device__ __forceinline__ void mfma_16x16x32(const i32x4& a, const i32x4& b) { 
 // wait state the load needs after it), global address base + offset[lane].  One statement, so nothing
 // can come between the write of M0 and the load; the scalar base + 32-bit lane offset form of the load
 // needs no 64-bit vector addition (the builtin's flat-pointer form costs one per load).
-template <int R, int LDS_IMM>
+// CPOL: cache-policy bits of the load (0 = default, 1 = nt, 2 = sc0, 3 = sc1, 4 = sc0 sc1; build-time experiments).
+#ifndef MOE_CPOL_A
+#define MOE_CPOL_A 0
+#endif
+#ifndef MOE_CPOL_B
+#define MOE_CPOL_B 0
+#endif
+#define MOE_MFMA_THEN_LOAD(MODIFIERS)                                                                                          \
+    asm volatile("s_add_i32 m0, %4, %5\n\tv_mfma_f32_16x16x32_bf16 a[%6:%7], %0, %1, a[%6:%7]\n\tglobal_load_lds_dwordx4 %2, %3" MODIFIERS \
+                 ::"v"(a), "v"(b), "v"(offset), "s"(base), "s"(lds_base), "n"(LDS_IMM), "n"(R), "n"(R + 3)                      \
+                 : "memory", "m0")
+template <int R, int LDS_IMM, int CPOL = 0>
 __device__ __forceinline__ void mfma_16x16x32_then_load(const i32x4& a, const i32x4& b, const char* base, uint32_t offset, uint32_t lds_base) {
 #ifdef __HIP_DEVICE_COMPILE__
-    asm volatile("s_add_i32 m0, %4, %5\n\tv_mfma_f32_16x16x32_bf16 a[%6:%7], %0, %1, a[%6:%7]\n\tglobal_load_lds_dwordx4 %2, %3"
-                 ::"v"(a), "v"(b), "v"(offset), "s"(base), "s"(lds_base), "n"(LDS_IMM), "n"(R), "n"(R + 3)
-                 : "memory", "m0");
+    if constexpr (CPOL == 0) MOE_MFMA_THEN_LOAD("");
+    else if constexpr (CPOL == 1) MOE_MFMA_THEN_LOAD(" nt");
+    else if constexpr (CPOL == 2) MOE_MFMA_THEN_LOAD(" sc0");
+    else if constexpr (CPOL == 3) MOE_MFMA_THEN_LOAD(" sc1");
+    else MOE_MFMA_THEN_LOAD(" sc0 sc1");
 #endif
 }
 // The same MFMA with its accumulator tile in vector registers the compiler allocates, and a plain 16-byte load
@@ -227,7 +240,8 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     MOE_TL_STAMP();
 #endif
     if (p.stagger_ticks > 0 && (blockIdx.x >> 3) < 32) {       // the first block of a compute unit
-        const int unit = p.stagger_mode == 0 ? (tc.mt & 3) : p.stagger_mode == 1 ? (int)((blockIdx.x >> 3) & 31) : (int)(((blockIdx.x >> 3) >> 2) & 7);
+        const int unit = p.stagger_mode == 0 ? (tc.mt & 3) : p.stagger_mode == 1 ? (int)((blockIdx.x >> 3) & 31)
+                       : p.stagger_mode == 2 ? (int)(((blockIdx.x >> 3) >> 2) & 7) : (int)(blockIdx.x & 7);
         const long long until = wall_clock64() + (long long)unit * p.stagger_ticks;
         for (int spin = 0; spin < 100000 && wall_clock64() < until; ++spin) __builtin_amdgcn_s_sleep(4);
     }
@@ -294,11 +308,15 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     }
     const char* a_ptr = p.a_gather ? p.A : p.A + (int64_t)row0 * p.lda_bytes;    // + 128 bytes per k-step
     int a_wr = kRingA;                                         // LDS offset of the activation stage being filled
-    // A tall tile (up to 32 rows more than BM: its share of the remainder of its expert's rows): wavefront row wm also
-    // computes the 16 rows BM + wm*16 .. against its column fragments, which are in registers anyway.  The
-    // activation fragment of those rows comes straight from memory (16 bytes per lane and half-step, four
-    // half-steps ahead), the eight accumulator tiles live in vector registers.
+    // A tall tile (up to 32 rows more than BM: its share of the remainder of its expert's rows).  The extra rows are
+    // multiplied against the column fragments the wavefronts hold in registers anyway; their activation fragment comes
+    // straight from memory (16 bytes per lane and half-step, four half-steps ahead), their accumulator tiles live in
+    // vector registers.  More than 16 extra rows: wavefront row wm computes the 16 rows BM + wm*16 .. against all its
+    // column fragments (8 more MFMAs per half-step in the 256-column block).  At most 16 extra rows: one 16-row MFMA
+    // tile, rows BM .. BM + 15, and the two wavefront rows - which hold the same column fragments - take half of the
+    // column fragments each (4 more MFMAs per half-step): split_extra.
     const int extra = rows_here > BM ? rows_here - BM : 0;
+    const bool split_extra = extra > 0 && extra <= 16;
     const char* ae_ptr = p.A;
     i32x4 AE[4];
     f32x4 accE[NJ];
@@ -307,10 +325,14 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) AE[u] = i32x4{0, 0, 0, 0};
     if (extra) {
-        const int er = min(BM + wm * 16 + (lane & 15), rows_here - 1);
+        const int er = min(BM + (split_extra ? 0 : wm * 16) + (lane & 15), rows_here - 1);
         const int64_t src = p.a_gather ? (int64_t)min(max(p.a_gather[row0 + er] / p.a_div, 0), p.a_rows - 1) : (int64_t)row0 + er;
         ae_ptr = p.A + src * p.lda_bytes + (lane >> 4) * 16;      // + 64 bytes per half-step
     }
+    // the column fragments of wavefront row W in a split extra tile: MODE 0 pairs gate fragment j with up fragment j + 4
+    // (the SwiGLU product needs both in one lane), so W takes the gate fragments 2W, 2W + 1 and their up fragments;
+    // MODE 1: the half W of the fragments
+    auto split_frag = [](int W, int t) constexpr { return MODE == 0 ? (t < 2 ? 2 * W + t : 4 + 2 * W + (t - 2)) : W * (NJ / 2) + t; };
     const uint32_t b_off = wave * 1024 + lane * 16;            // weight half-tiles are copied linearly
 
     // The loads issued during half-step h: activation instructions (h & 1) * 4 + i (i = 0..3) of the
@@ -384,13 +406,13 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     };
     auto mfma_load_a = [&](auto i_c, auto j_c, const i32x4& a, const i32x4& b, auto ia_c) __attribute__((always_inline)) {   // + activation load instruction IA
         constexpr int IA = decltype(ia_c)::value;
-        mfma_16x16x32_then_load<(decltype(i_c)::value * NJ + decltype(j_c)::value) * 4, IA * kWaves * 1024>(a, b, a_ptr, a_off[IA], a_wr_w);
+        mfma_16x16x32_then_load<(decltype(i_c)::value * NJ + decltype(j_c)::value) * 4, IA * kWaves * 1024, MOE_CPOL_A>(a, b, a_ptr, a_off[IA], a_wr_w);
         advance_a(IA);
     };
     auto mfma_load_b = [&](auto i_c, auto j_c, const i32x4& a, const i32x4& b, auto slot_c, auto l_c, int kn) __attribute__((always_inline)) {   // + weight load instruction L of half-step kn into slot SLOT
         constexpr int SLOT = decltype(slot_c)::value, I = decltype(l_c)::value;
         constexpr int odd = SLOT & 1;               // S is even: the parity of the half-step is that of its slot
-        mfma_16x16x32_then_load<(decltype(i_c)::value * NJ + decltype(j_c)::value) * 4, SLOT * kStageB + (I >= 2 ? kHalfTile : 0) + (I & 1) * (kWaves * 1024)>(
+        mfma_16x16x32_then_load<(decltype(i_c)::value * NJ + decltype(j_c)::value) * 4, SLOT * kStageB + (I >= 2 ? kHalfTile : 0) + (I & 1) * (kWaves * 1024), MOE_CPOL_B>(
             a, b, (I < 2 ? w0 : w1).tile, b_voff[odd][I & 1], lds_wave);
         advance_b(kn, odd, I);
     };
@@ -476,8 +498,15 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                     }
                 });
                 if (__builtin_expect(extra != 0, 0)) {       // tall tile: the extra row tile against the column fragments of k
+                    asm volatile("" : "+v"(AE[U]));           // its loaded value is used from here on (behind the wait above)
+                    if (!split_extra) {
 #pragma unroll
-                    for (int jj = 0; jj < NJ; ++jj) mfma_16x16x32_v(accE[jj], AE[U], BF[HP][jj]);
+                        for (int jj = 0; jj < NJ; ++jj) mfma_16x16x32_v(accE[jj], AE[U], BF[HP][jj]);
+                    } else if (wm == 0) {
+                        static_for<NJ / 2>([&](auto tc_) __attribute__((always_inline)) { constexpr int j = split_frag(0, decltype(tc_)::value); mfma_16x16x32_v(accE[j], AE[U], BF[HP][j]); });
+                    } else {
+                        static_for<NJ / 2>([&](auto tc_) __attribute__((always_inline)) { constexpr int j = split_frag(1, decltype(tc_)::value); mfma_16x16x32_v(accE[j], AE[U], BF[HP][j]); });
+                    }
                     MOE_FENCE();
                     if (k + 4 < KH) load_vgpr_16(AE[U], ae_ptr + (int64_t)(k + 4) * 64);
                     MOE_FENCE();
@@ -646,14 +675,15 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         } else if (row_tiles == 2) store_rows(std::false_type{}, std::integral_constant<int, 2>{});
         else if (row_tiles == 4) store_rows(std::false_type{}, std::integral_constant<int, 4>{});
         else store_rows(std::false_type{}, std::integral_constant<int, 8>{});
-        if (extra) {                           // the extra row tile of a tall tile
+        if (extra) {                           // the extra row tile of a tall tile (split: this wavefront row's column fragments only)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int row = BM + wm * 16 + (lane >> 4) * 4 + r;
+                const int row = BM + (split_extra ? 0 : wm * 16) + (lane >> 4) * 4 + r;
                 if (row < rows_here) {
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        h[(int64_t)row * p.ldo + j * 16] = (__bf16)silu_mul(accE[j][r], accE[j + 4][r]);
+                        if (!split_extra || (j >> 1) == wm)
+                            h[(int64_t)row * p.ldo + j * 16] = (__bf16)silu_mul(accE[j][r], accE[j + 4][r]);
                 }
             }
         }
@@ -689,14 +719,15 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
             } else if (row_tiles == 2) store_rows(std::false_type{}, std::integral_constant<int, 2>{});
             else if (row_tiles == 4) store_rows(std::false_type{}, std::integral_constant<int, 4>{});
             else store_rows(std::false_type{}, std::integral_constant<int, 8>{});
-            if (extra) {                       // the extra row tile of a tall tile
+            if (extra) {                       // the extra row tile of a tall tile (split: this wavefront row's column fragments only)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int row = BM + wm * 16 + (lane >> 4) * 4 + r;
+                    const int row = BM + (split_extra ? 0 : wm * 16) + (lane >> 4) * 4 + r;
                     if (row < rows_here) {
                         const float wr = sw[row];
 #pragma unroll
-                        for (int j = 0; j < NJ; ++j) o[(int64_t)row * p.ldo + j * 16] = accE[j][r] * wr;
+                        for (int j = 0; j < NJ; ++j)
+                            if (!split_extra || j / (NJ / 2) == wm) o[(int64_t)row * p.ldo + j * 16] = accE[j][r] * wr;
                     }
                 }
             }
@@ -796,6 +827,9 @@ int launch_linear_bf16(const LinearArgs& a, hipStream_t st) {
     p.xcd_remap = get_opt(OPT_XCD_REMAP);
     p.half_tiles = get_opt(OPT_HALF_TILES);
     p.tall_rows = get_opt(OPT_TALL_TILES) ? 32 : 0;
+    p.tall_first = get_opt(OPT_TALL_FIRST);
+    p.tall_split = get_opt(OPT_TALL_SPLIT);
+    p.chunked = std::min(std::max(get_opt(OPT_CHUNKED), 0), 32);
     const int wide_tiles = (p.n_page_tiles + 1) / 2;
     if ((int64_t)(a.T / BM + 1) * wide_tiles < 2 * kComputeUnits) {       // too few 256-wide tiles to fill the chip
         p.NT = p.n_page_tiles;

@@ -34,6 +34,9 @@ struct GemmParams {
     const int32_t* a_gather;  // bf16 kernel, or null: row r of A is row a_gather[r] / a_div of the matrix at A (a_rows rows)
     int32_t a_div, a_rows;
     int32_t tall_rows;        // bf16 kernel: a row tile may be up to this many rows higher than BM (0 or 32), see locate_tile
+    int32_t tall_split;       // bf16 kernel: a remainder prefers tall tiles with at most 16 extra rows, see tall_tiles_of
+    int32_t chunked;          // tile numbering: groups dealt to the XCDs in chunks of about this many tiles (0: single groups), see locate_tile
+    int32_t tall_first;       // bf16 kernel: tile numbering with the tall tiles of a chunk of groups first, see locate_tile
     int32_t stagger_ticks;    // bf16 kernel: start delay unit of a compute unit's first block, in ticks of the 100 MHz counter
     int32_t stagger_mode;
 };
@@ -44,15 +47,17 @@ struct TileCoord {
 };
 
 // Tile order.  The row tiles of one column tile of one expert form a GROUP (they share
-// the weight tiles); groups are numbered expert by expert, column tile by column tile.
-// With xcd_remap the groups are dealt round robin to the 8 XCDs (block b runs on XCD
-// b % 8, each with its own L2): XCD x works through the groups x, x + 8, x + 16, ...
-// row tile by row tile, so the blocks an XCD runs at the same time are the row tiles of a
-// few column tiles of one expert, and every XCD gets the same mix of experts, hence of
-// full and partial row tiles (contiguous chunks of the numbering gave one XCD 22 % more
-// full tiles than another on the Mixtral-8x7B-shaped workload).  Without it block b takes
-// tile b of the plain numbering.  The tile counts come from offsets[], so the grid is only
-// an upper bound and surplus blocks leave at once.
+// the weight tiles); the groups of an expert are taken in CHUNKS of G consecutive column
+// tiles, G = max(1, 32 / row tiles of the expert): about as many tiles as an XCD has compute
+// units.  With xcd_remap the chunks, numbered expert by expert, are dealt round robin to the
+// 8 XCDs (block b runs on XCD b % 8, each with its own L2): the blocks an XCD runs at the
+// same time are then the row tiles of G column tiles of ONE expert, so an activation row tile
+// is fetched into that L2 once for G blocks and a weight tile once for all its row tiles
+// (dealing single groups round robin left only NT / 8 groups of an expert on an XCD: two in
+// the down projection of the Mixtral-8x7B shape, where every activation row tile then crossed
+// the fabric once per pair of blocks).  Without xcd_remap all chunks belong to one sequence.
+// The tile counts come from offsets[], so the grid is only an upper bound and surplus blocks
+// leave at once.
 //
 // Every wavefront does the search on its own, one expert per lane (at most 64
 // experts): one load of the segment bounds, prefix sums of the tile counts over
@@ -67,6 +72,15 @@ __device__ __forceinline__ int lane_prefix_sum(int v, int lane) {
     return v;
 }
 
+// Tall tiles that take a remainder of r rows along with q full tiles (0 < r <= tall_rows * q).  A tall tile with at
+// most 16 extra rows costs half of what one with 17..32 costs (bf16 kernel), so with tall_split the remainder goes to
+// ceil(r / 16) tiles when there are that many, else to as few tiles as possible (ceil(r / tall_rows)).
+__device__ __forceinline__ int tall_tiles_of(int r, int q, int tall_rows, int tall_split) {
+    const int m16 = (r + 15) / 16;
+    if (tall_split && m16 <= q) return m16;
+    return (r + tall_rows - 1) / tall_rows;
+}
+
 template <int BM>
 __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     TileCoord t{};
@@ -79,36 +93,71 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
         cnt = p.offsets[e_l + 1] - seg0;
     }
     const int stride = p.xcd_remap ? 8 : 1;
-    const int x = p.xcd_remap ? (int)(blockIdx.x & 7) : 0;           // my groups: x, x + stride, ...
-    const int idx = p.xcd_remap ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;    // my position among their row tiles
-    // groups of mine below group number n: ceil((n - x) / stride) for n >= 0 (0 <= x < stride)
-    const int g_lo = lane * p.NT, g_hi = g_lo + p.NT;              // group numbers of my lane's expert
-    const int c_lo = (g_lo - x + stride - 1) / stride, c_hi = (g_hi - x + stride - 1) / stride;
+    const int x = p.xcd_remap ? (int)(blockIdx.x & 7) : 0;           // my chunks: those whose number is x modulo stride
+    const int idx = p.xcd_remap ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;    // my position among their tiles
     // row tiles of my lane's expert.  q full tiles and a remainder r: when r <= tall_rows * q the remainder is
     // spread over the last ceil(r / tall_rows) of the q tiles (each at most BM + tall_rows rows high: as few
     // tall tiles as possible, every one costs an extra 16-row MFMA tile per wavefront), otherwise it is a tile
     // of its own
     const int q_l = cnt / BM, r_l = cnt - q_l * BM;
-    const int mtiles_l = (q_l >= 1 && r_l <= p.tall_rows * q_l) ? q_l : q_l + (r_l > 0);
-    const int tiles_l = (c_hi - c_lo) * mtiles_l;
+    const bool rides_l = q_l >= 1 && r_l > 0 && r_l <= p.tall_rows * q_l;
+    const int mtiles_l = rides_l ? q_l : q_l + (r_l > 0);
+    const int tall_l = rides_l ? tall_tiles_of(r_l, q_l, p.tall_rows, p.tall_split) : 0;
+    // chunks of my lane's expert: nch_l of G_l groups each, the last one of last_l groups; an expert without rows has none
+    const int G_l = p.chunked ? max(1, p.chunked / max(mtiles_l, 1)) : 1;      // p.chunked: tiles a chunk aims at (32)
+    const int nch_l = mtiles_l > 0 ? (p.NT + G_l - 1) / G_l : 0;
+    const int last_l = p.NT - (nch_l - 1) * G_l;
+    const int cb_l = lane_prefix_sum(nch_l, lane) - nch_l;          // chunks of the experts before mine
+    int c0_l = (x - cb_l) % stride;                                  // my first chunk in this expert
+    if (c0_l < 0) c0_l += stride;
+    const int mine_l = c0_l < nch_l ? (nch_l - 1 - c0_l) / stride + 1 : 0;
+    const bool last_mine_l = mine_l > 0 && (c0_l + (mine_l - 1) * stride == nch_l - 1);
+    const int groups_l = mine_l * G_l - (last_mine_l ? G_l - last_l : 0);
+    const int tiles_l = groups_l * mtiles_l;
     const int incl = lane_prefix_sum(tiles_l, lane);
     if (idx >= __builtin_amdgcn_readlane(incl, 63)) return t;
     const unsigned long long holds = __ballot(idx < incl);           // lanes of this and later experts
     const int src = __builtin_amdgcn_readfirstlane(__ffsll((long long)holds) - 1);
     const int mtiles = __builtin_amdgcn_readfirstlane(__shfl(mtiles_l, src, 64));
+    const int tall = __builtin_amdgcn_readfirstlane(__shfl(tall_l, src, 64));
+    const int G = __builtin_amdgcn_readfirstlane(__shfl(G_l, src, 64));
+    const int nch = __builtin_amdgcn_readfirstlane(__shfl(nch_l, src, 64));
+    const int last = __builtin_amdgcn_readfirstlane(__shfl(last_l, src, 64));
+    const int c0 = __builtin_amdgcn_readfirstlane(__shfl(c0_l, src, 64));
     const int before = __builtin_amdgcn_readfirstlane(__shfl(incl - tiles_l, src, 64));
-    const int first = __builtin_amdgcn_readfirstlane(__shfl(c_lo, src, 64));       // my groups before this expert
     const int seg = __builtin_amdgcn_readfirstlane(__shfl(seg0, src, 64));
     const int rows = __builtin_amdgcn_readfirstlane(__shfl(cnt, src, 64));
     const int rem = idx - before;
-    const int j = rem / mtiles;                                        // my j-th group inside this expert
+    // my chunks before the last one of the expert are full (G groups of mtiles tiles)
+    const int ci = rem / (G * mtiles);
+    const int c = c0 + ci * stride;                                  // chunk number inside the expert
+    const int g_c = c == nch - 1 ? last : G;                         // its groups
+    const int r2 = rem - ci * G * mtiles;                            // my tile inside the chunk
+    // Order inside a chunk.  Blocks are handed to compute units first come, first served, and a tall tile
+    // takes longer than the others.  The tall tiles of all groups of the chunk come first, then the other
+    // tiles group by group: the compute units that arrive first get the long tiles, those that arrive late
+    // (they had a long tile the last time) get ordinary ones, and the blocks that run at the same time keep
+    // reading the same stretch of the operands they share.  Numbered with the tall tile last in its group,
+    // the late compute units would meet the next tall tile again and fall further behind with every round.
+    int jj, mt;
+    if (p.tall_first && tall > 0 && r2 < g_c * tall) {
+        jj = r2 / tall;
+        mt = (mtiles - tall) + (r2 - jj * tall);
+    } else if (p.tall_first && tall > 0) {
+        const int r3 = r2 - g_c * tall, plain = mtiles - tall;       // plain >= 1: tiles remain behind the tall ones
+        jj = r3 / plain;
+        mt = r3 - jj * plain;
+    } else {
+        jj = r2 / mtiles;
+        mt = r2 - jj * mtiles;
+    }
+    t.nt = c * G + jj;
+    t.mt = mt;
     t.e = p.e_begin + src;
-    t.nt = x + (first + j) * stride - src * p.NT;
-    t.mt = rem - j * mtiles;
     const int q = rows / BM, r = rows - q * BM;
     if (r > 0 && q >= 1 && r <= p.tall_rows * q) {
         // the last m tiles are BM + r / m rows high, the first r % m of them one row more
-        const int m = (r + p.tall_rows - 1) / p.tall_rows, plain = q - m;
+        const int m = tall_tiles_of(r, q, p.tall_rows, p.tall_split), plain = q - m;
         const int i = t.mt - plain;
         if (i < 0) {
             t.row0 = seg + t.mt * BM;
@@ -139,11 +188,15 @@ __device__ __forceinline__ const char* tile_address(const GemmParams& p, const i
     return p.pool + (int64_t)slot * p.page_bytes + (int64_t)within * p.tile_bytes;
 }
 
-// grid size that covers every tile for any routing result: an XCD gets at most ceil(NT / 8) of an
-// expert's NT groups, each with that expert's row tiles
+// Grid size that covers every tile for any routing result.  Total tiles <= NT * M with M = R / BM + n_experts
+// (>= the sum over the experts of their row tiles).  Dealt in chunks, an XCD gets from an expert at most
+// ceil(chunks / 8) chunks, i.e. at most an eighth of that expert's tiles plus two chunks' worth; a chunk has at
+// most max(32, row tiles of the expert) tiles.
 inline int gemm_grid(int NT, int R, int BM, int n_experts) {
-    const int m_tiles_max = R / BM + n_experts;   // >= sum over experts of ceil(rows / BM)
-    return 8 * ((NT + 7) / 8) * m_tiles_max;
+    const int64_t M = R / BM + n_experts;
+    const int64_t per_xcd = ((int64_t)NT * M + 7) / 8 + 2 * (32 * (int64_t)n_experts + M);
+    const int64_t plain = 8 * (((int64_t)NT + 7) / 8) * M;            // single groups dealt round robin (chunked = 0), or no dealing at all
+    return (int)std::max(8 * per_xcd, plain);
 }
 
 inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const FfnArgs& a) {
@@ -162,6 +215,9 @@ inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const 
     p.xcd_remap = get_opt(OPT_XCD_REMAP);
     p.half_tiles = get_opt(OPT_HALF_TILES);
     p.tall_rows = (s.dtype == MOE_DTYPE_BF16 && get_opt(OPT_TALL_TILES)) ? 32 : 0;
+    p.tall_first = get_opt(OPT_TALL_FIRST);
+    p.tall_split = get_opt(OPT_TALL_SPLIT);
+    p.chunked = std::min(std::max(get_opt(OPT_CHUNKED), 0), 32);      // the grid bound assumes chunks of at most max(32, row tiles) tiles
     p.stagger_ticks = get_opt(OPT_STAGGER_NS) / 10;
     p.stagger_mode = get_opt(OPT_STAGGER_MODE);
 }
