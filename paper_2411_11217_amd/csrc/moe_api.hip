@@ -21,12 +21,11 @@ static int g_opts[OPT_COUNT] = {
     /*OPT_FUSE_GATHER*/ 1,   // 1: the bf16 gate/up GEMM of moe_layer reads the rows of x through row_src (no x_perm copy)
     /*OPT_TALL_TILES*/ 1,    // 1: bf16: row tiles may be up to 32 rows higher than 256 (a small remainder needs no tile of its own)
     /*OPT_TALL_FIRST*/ 1,    // 1: bf16 tile numbering: inside a chunk of column-tile groups the tall row tiles come first
-    /*OPT_TALL_SPLIT*/ 1,    // 1: bf16: a remainder is spread so that tall tiles have at most 16 extra rows when there are enough tiles
     /*OPT_CHUNKED*/ 32,      // tile numbering: the column-tile groups of an expert go to the XCDs in chunks of about this many tiles (at most 32; 0: single groups)
     /*OPT_STAGGER_NS*/ 0,    // bf16 expert GEMMs: the first block of every compute unit starts this many ns x its stagger unit late
     /*OPT_STAGGER_MODE*/ 0,  // stagger unit: 0 = row tile index, 1 = position among the 32 blocks of the XCD, 2 = column tile group
 };
-static const char* g_opt_names[OPT_COUNT] = {"xcd_remap", "profile", "down_cols", "half_tiles", "fuse_gather", "tall_tiles", "tall_first", "tall_split", "chunked", "stagger_ns", "stagger_mode"};
+static const char* g_opt_names[OPT_COUNT] = {"xcd_remap", "profile", "down_cols", "half_tiles", "fuse_gather", "tall_tiles", "tall_first", "chunked", "stagger_ns", "stagger_mode"};
 int get_opt(int id) { return g_opts[id]; }
 
 int validate_shape(const moe_shape* s) {

@@ -308,15 +308,17 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     }
     const char* a_ptr = p.a_gather ? p.A : p.A + (int64_t)row0 * p.lda_bytes;    // + 128 bytes per k-step
     int a_wr = kRingA;                                         // LDS offset of the activation stage being filled
-    // A tall tile (up to 32 rows more than BM: its share of the remainder of its expert's rows).  The extra rows are
-    // multiplied against the column fragments the wavefronts hold in registers anyway; their activation fragment comes
-    // straight from memory (16 bytes per lane and half-step, four half-steps ahead), their accumulator tiles live in
-    // vector registers.  More than 16 extra rows: wavefront row wm computes the 16 rows BM + wm*16 .. against all its
-    // column fragments (8 more MFMAs per half-step in the 256-column block).  At most 16 extra rows: one 16-row MFMA
-    // tile, rows BM .. BM + 15, and the two wavefront rows - which hold the same column fragments - take half of the
-    // column fragments each (4 more MFMAs per half-step): split_extra.
+    // A tall tile (up to 32 rows more than BM: its share of the remainder of its expert's rows): wavefront row wm also
+    // computes the 16 rows BM + wm*16 .. against its column fragments, which are in registers anyway.  The
+    // activation fragment of those rows comes straight from memory (16 bytes per lane and half-step, four
+    // half-steps ahead), the eight accumulator tiles live in vector registers.
+    // These accumulators and the loaded fragment are values the compiler allocates, and it knows neither that the
+    // asm statements that write them are an MFMA (result lands passes later) nor a load (result lands much later):
+    // it must never have a reason to copy them.  Any control flow around their uses makes it merge values with
+    // register copies next to the asm statements, which then read registers still being written (seen as wrong
+    // extra rows when the MFMAs of this block were put under a branch on the number of extra rows).  So: one
+    // unconditional sequence per half-step under the single test of `extra`, nothing else.
     const int extra = rows_here > BM ? rows_here - BM : 0;
-    const bool split_extra = extra > 0 && extra <= 16;
     const char* ae_ptr = p.A;
     i32x4 AE[4];
     f32x4 accE[NJ];
@@ -325,14 +327,10 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) AE[u] = i32x4{0, 0, 0, 0};
     if (extra) {
-        const int er = min(BM + (split_extra ? 0 : wm * 16) + (lane & 15), rows_here - 1);
+        const int er = min(BM + wm * 16 + (lane & 15), rows_here - 1);
         const int64_t src = p.a_gather ? (int64_t)min(max(p.a_gather[row0 + er] / p.a_div, 0), p.a_rows - 1) : (int64_t)row0 + er;
         ae_ptr = p.A + src * p.lda_bytes + (lane >> 4) * 16;      // + 64 bytes per half-step
     }
-    // the column fragments of wavefront row W in a split extra tile: MODE 0 pairs gate fragment j with up fragment j + 4
-    // (the SwiGLU product needs both in one lane), so W takes the gate fragments 2W, 2W + 1 and their up fragments;
-    // MODE 1: the half W of the fragments
-    auto split_frag = [](int W, int t) constexpr { return MODE == 0 ? (t < 2 ? 2 * W + t : 4 + 2 * W + (t - 2)) : W * (NJ / 2) + t; };
     const uint32_t b_off = wave * 1024 + lane * 16;            // weight half-tiles are copied linearly
 
     // The loads issued during half-step h: activation instructions (h & 1) * 4 + i (i = 0..3) of the
@@ -498,15 +496,8 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                     }
                 });
                 if (__builtin_expect(extra != 0, 0)) {       // tall tile: the extra row tile against the column fragments of k
-                    asm volatile("" : "+v"(AE[U]));           // its loaded value is used from here on (behind the wait above)
-                    if (!split_extra) {
 #pragma unroll
-                        for (int jj = 0; jj < NJ; ++jj) mfma_16x16x32_v(accE[jj], AE[U], BF[HP][jj]);
-                    } else if (wm == 0) {
-                        static_for<NJ / 2>([&](auto tc_) __attribute__((always_inline)) { constexpr int j = split_frag(0, decltype(tc_)::value); mfma_16x16x32_v(accE[j], AE[U], BF[HP][j]); });
-                    } else {
-                        static_for<NJ / 2>([&](auto tc_) __attribute__((always_inline)) { constexpr int j = split_frag(1, decltype(tc_)::value); mfma_16x16x32_v(accE[j], AE[U], BF[HP][j]); });
-                    }
+                    for (int jj = 0; jj < NJ; ++jj) mfma_16x16x32_v(accE[jj], AE[U], BF[HP][jj]);
                     MOE_FENCE();
                     if (k + 4 < KH) load_vgpr_16(AE[U], ae_ptr + (int64_t)(k + 4) * 64);
                     MOE_FENCE();
@@ -675,15 +666,14 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         } else if (row_tiles == 2) store_rows(std::false_type{}, std::integral_constant<int, 2>{});
         else if (row_tiles == 4) store_rows(std::false_type{}, std::integral_constant<int, 4>{});
         else store_rows(std::false_type{}, std::integral_constant<int, 8>{});
-        if (extra) {                           // the extra row tile of a tall tile (split: this wavefront row's column fragments only)
+        if (extra) {                           // the extra row tile of a tall tile
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int row = BM + (split_extra ? 0 : wm * 16) + (lane >> 4) * 4 + r;
+                const int row = BM + wm * 16 + (lane >> 4) * 4 + r;
                 if (row < rows_here) {
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        if (!split_extra || (j >> 1) == wm)
-                            h[(int64_t)row * p.ldo + j * 16] = (__bf16)silu_mul(accE[j][r], accE[j + 4][r]);
+                        h[(int64_t)row * p.ldo + j * 16] = (__bf16)silu_mul(accE[j][r], accE[j + 4][r]);
                 }
             }
         }
@@ -719,15 +709,14 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
             } else if (row_tiles == 2) store_rows(std::false_type{}, std::integral_constant<int, 2>{});
             else if (row_tiles == 4) store_rows(std::false_type{}, std::integral_constant<int, 4>{});
             else store_rows(std::false_type{}, std::integral_constant<int, 8>{});
-            if (extra) {                       // the extra row tile of a tall tile (split: this wavefront row's column fragments only)
+            if (extra) {                       // the extra row tile of a tall tile
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int row = BM + (split_extra ? 0 : wm * 16) + (lane >> 4) * 4 + r;
+                    const int row = BM + wm * 16 + (lane >> 4) * 4 + r;
                     if (row < rows_here) {
                         const float wr = sw[row];
 #pragma unroll
-                        for (int j = 0; j < NJ; ++j)
-                            if (!split_extra || j / (NJ / 2) == wm) o[(int64_t)row * p.ldo + j * 16] = accE[j][r] * wr;
+                        for (int j = 0; j < NJ; ++j) o[(int64_t)row * p.ldo + j * 16] = accE[j][r] * wr;
                     }
                 }
             }
@@ -828,7 +817,6 @@ int launch_linear_bf16(const LinearArgs& a, hipStream_t st) {
     p.half_tiles = get_opt(OPT_HALF_TILES);
     p.tall_rows = get_opt(OPT_TALL_TILES) ? 32 : 0;
     p.tall_first = get_opt(OPT_TALL_FIRST);
-    p.tall_split = get_opt(OPT_TALL_SPLIT);
     p.chunked = std::min(std::max(get_opt(OPT_CHUNKED), 0), 32);
     const int wide_tiles = (p.n_page_tiles + 1) / 2;
     if ((int64_t)(a.T / BM + 1) * wide_tiles < 2 * kComputeUnits) {       // too few 256-wide tiles to fill the chip

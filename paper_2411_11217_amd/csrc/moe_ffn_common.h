@@ -34,7 +34,6 @@ struct GemmParams {
     const int32_t* a_gather;  // bf16 kernel, or null: row r of A is row a_gather[r] / a_div of the matrix at A (a_rows rows)
     int32_t a_div, a_rows;
     int32_t tall_rows;        // bf16 kernel: a row tile may be up to this many rows higher than BM (0 or 32), see locate_tile
-    int32_t tall_split;       // bf16 kernel: a remainder prefers tall tiles with at most 16 extra rows, see tall_tiles_of
     int32_t chunked;          // tile numbering: groups dealt to the XCDs in chunks of about this many tiles (0: single groups), see locate_tile
     int32_t tall_first;       // bf16 kernel: tile numbering with the tall tiles of a chunk of groups first, see locate_tile
     int32_t stagger_ticks;    // bf16 kernel: start delay unit of a compute unit's first block, in ticks of the 100 MHz counter
@@ -72,15 +71,6 @@ __device__ __forceinline__ int lane_prefix_sum(int v, int lane) {
     return v;
 }
 
-// Tall tiles that take a remainder of r rows along with q full tiles (0 < r <= tall_rows * q).  A tall tile with at
-// most 16 extra rows costs half of what one with 17..32 costs (bf16 kernel), so with tall_split the remainder goes to
-// ceil(r / 16) tiles when there are that many, else to as few tiles as possible (ceil(r / tall_rows)).
-__device__ __forceinline__ int tall_tiles_of(int r, int q, int tall_rows, int tall_split) {
-    const int m16 = (r + 15) / 16;
-    if (tall_split && m16 <= q) return m16;
-    return (r + tall_rows - 1) / tall_rows;
-}
-
 template <int BM>
 __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     TileCoord t{};
@@ -102,7 +92,7 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     const int q_l = cnt / BM, r_l = cnt - q_l * BM;
     const bool rides_l = q_l >= 1 && r_l > 0 && r_l <= p.tall_rows * q_l;
     const int mtiles_l = rides_l ? q_l : q_l + (r_l > 0);
-    const int tall_l = rides_l ? tall_tiles_of(r_l, q_l, p.tall_rows, p.tall_split) : 0;
+    const int tall_l = rides_l ? (r_l + p.tall_rows - 1) / p.tall_rows : 0;
     // chunks of my lane's expert: nch_l of G_l groups each, the last one of last_l groups; an expert without rows has none
     const int G_l = p.chunked ? max(1, p.chunked / max(mtiles_l, 1)) : 1;      // p.chunked: tiles a chunk aims at (32)
     const int nch_l = mtiles_l > 0 ? (p.NT + G_l - 1) / G_l : 0;
@@ -157,7 +147,7 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     const int q = rows / BM, r = rows - q * BM;
     if (r > 0 && q >= 1 && r <= p.tall_rows * q) {
         // the last m tiles are BM + r / m rows high, the first r % m of them one row more
-        const int m = tall_tiles_of(r, q, p.tall_rows, p.tall_split), plain = q - m;
+        const int m = (r + p.tall_rows - 1) / p.tall_rows, plain = q - m;
         const int i = t.mt - plain;
         if (i < 0) {
             t.row0 = seg + t.mt * BM;
@@ -216,7 +206,6 @@ inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const 
     p.half_tiles = get_opt(OPT_HALF_TILES);
     p.tall_rows = (s.dtype == MOE_DTYPE_BF16 && get_opt(OPT_TALL_TILES)) ? 32 : 0;
     p.tall_first = get_opt(OPT_TALL_FIRST);
-    p.tall_split = get_opt(OPT_TALL_SPLIT);
     p.chunked = std::min(std::max(get_opt(OPT_CHUNKED), 0), 32);      // the grid bound assumes chunks of at most max(32, row tiles) tiles
     p.stagger_ticks = get_opt(OPT_STAGGER_NS) / 10;
     p.stagger_mode = get_opt(OPT_STAGGER_MODE);
