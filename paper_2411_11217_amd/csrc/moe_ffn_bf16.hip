@@ -767,7 +767,7 @@ int launch_expert_ffn_bf16(const moe_shape& s, const Geom& g, const FfnArgs& a, 
     GemmParams p{};
     fill_common(p, s, g, a);
     fill_gate_up(p, s, g, a);
-    int rc = launch_stages<0, 2>(p, gemm_grid(p.NT, R, BM, n_exp), st);
+    int rc = launch_stages<0, 2>(p, gemm_grid(p.NT, R, BM, n_exp, p.chunked), st);
     if (rc != MOE_OK) return rc;
     if (a.mid_event) MOE_HIP_TRY(hipEventRecord(a.mid_event, st));
     fill_down(p, s, g, a);
@@ -783,9 +783,9 @@ int launch_expert_ffn_bf16(const moe_shape& s, const Geom& g, const FfnArgs& a, 
     const bool narrow = opt == 1 || (opt == 0 && n_exp * row_tiles_each * p.NT < kComputeUnits);
     if (narrow) {
         p.NT = (int32_t)g.dt;
-        return launch_stages<1, 1>(p, gemm_grid(p.NT, R, BM, n_exp), st);
+        return launch_stages<1, 1>(p, gemm_grid(p.NT, R, BM, n_exp, p.chunked), st);
     }
-    return launch_stages<1, 2>(p, gemm_grid(p.NT, R, BM, n_exp), st);
+    return launch_stages<1, 2>(p, gemm_grid(p.NT, R, BM, n_exp, p.chunked), st);
 }
 
 // y = x W^T for a dense weight matrix held as pages: the down-projection kernel with one "expert"
@@ -821,10 +821,10 @@ int launch_linear_bf16(const LinearArgs& a, hipStream_t st) {
     const int wide_tiles = (p.n_page_tiles + 1) / 2;
     if ((int64_t)(a.T / BM + 1) * wide_tiles < 2 * kComputeUnits) {       // too few 256-wide tiles to fill the chip
         p.NT = p.n_page_tiles;
-        return launch_stages<1, 1>(p, gemm_grid(p.NT, a.T, BM, 1), st);
+        return launch_stages<1, 1>(p, gemm_grid(p.NT, a.T, BM, 1, p.chunked), st);
     }
     p.NT = wide_tiles;
-    return launch_stages<1, 2>(p, gemm_grid(p.NT, a.T, BM, 1), st);
+    return launch_stages<1, 2>(p, gemm_grid(p.NT, a.T, BM, 1, p.chunked), st);
 }
 
 

@@ -93,16 +93,17 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     const bool rides_l = q_l >= 1 && r_l > 0 && r_l <= p.tall_rows * q_l;
     const int mtiles_l = rides_l ? q_l : q_l + (r_l > 0);
     const int tall_l = rides_l ? (r_l + p.tall_rows - 1) / p.tall_rows : 0;
-    // chunks of my lane's expert: nch_l of G_l groups each, the last one of last_l groups; an expert without rows has none
-    const int G_l = p.chunked ? max(1, p.chunked / max(mtiles_l, 1)) : 1;      // p.chunked: tiles a chunk aims at (32)
+    // chunks of my lane's expert: nch_l = ceil(NT / G) of them, of Gc_l or Gc_l + 1 groups each (the first big_l ones are
+    // the bigger: equal sizes keep the XCDs' shares equal when the groups do not divide); an expert without rows has none
+    const int G_l = (p.chunked && cnt > BM / 2) ? min(max(1, p.chunked / max(mtiles_l, 1)), 8) : 1;      // p.chunked: tiles a chunk aims at (32); at most 8 groups
     const int nch_l = mtiles_l > 0 ? (p.NT + G_l - 1) / G_l : 0;
-    const int last_l = p.NT - (nch_l - 1) * G_l;
+    const int Gc_l = p.NT / max(nch_l, 1), big_l = p.NT - Gc_l * nch_l;
     const int cb_l = lane_prefix_sum(nch_l, lane) - nch_l;          // chunks of the experts before mine
     int c0_l = (x - cb_l) % stride;                                  // my first chunk in this expert
     if (c0_l < 0) c0_l += stride;
     const int mine_l = c0_l < nch_l ? (nch_l - 1 - c0_l) / stride + 1 : 0;
-    const bool last_mine_l = mine_l > 0 && (c0_l + (mine_l - 1) * stride == nch_l - 1);
-    const int groups_l = mine_l * G_l - (last_mine_l ? G_l - last_l : 0);
+    const int bigmine_l = c0_l < big_l ? (big_l - 1 - c0_l) / stride + 1 : 0;      // my chunks among the bigger ones: my first ones
+    const int groups_l = mine_l * Gc_l + bigmine_l;
     const int tiles_l = groups_l * mtiles_l;
     const int incl = lane_prefix_sum(tiles_l, lane);
     if (idx >= __builtin_amdgcn_readlane(incl, 63)) return t;
@@ -110,19 +111,21 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     const int src = __builtin_amdgcn_readfirstlane(__ffsll((long long)holds) - 1);
     const int mtiles = __builtin_amdgcn_readfirstlane(__shfl(mtiles_l, src, 64));
     const int tall = __builtin_amdgcn_readfirstlane(__shfl(tall_l, src, 64));
-    const int G = __builtin_amdgcn_readfirstlane(__shfl(G_l, src, 64));
-    const int nch = __builtin_amdgcn_readfirstlane(__shfl(nch_l, src, 64));
-    const int last = __builtin_amdgcn_readfirstlane(__shfl(last_l, src, 64));
+    const int Gc = __builtin_amdgcn_readfirstlane(__shfl(Gc_l, src, 64));
+    const int big = __builtin_amdgcn_readfirstlane(__shfl(big_l, src, 64));
+    const int bigmine = __builtin_amdgcn_readfirstlane(__shfl(bigmine_l, src, 64));
     const int c0 = __builtin_amdgcn_readfirstlane(__shfl(c0_l, src, 64));
     const int before = __builtin_amdgcn_readfirstlane(__shfl(incl - tiles_l, src, 64));
     const int seg = __builtin_amdgcn_readfirstlane(__shfl(seg0, src, 64));
     const int rows = __builtin_amdgcn_readfirstlane(__shfl(cnt, src, 64));
     const int rem = idx - before;
-    // my chunks before the last one of the expert are full (G groups of mtiles tiles)
-    const int ci = rem / (G * mtiles);
+    // my chunks in their order: bigmine of Gc + 1 groups, then the others of Gc groups
+    const int in_big = bigmine * (Gc + 1) * mtiles;
+    const int ci = rem < in_big ? rem / ((Gc + 1) * mtiles) : bigmine + (rem - in_big) / (Gc * mtiles);
     const int c = c0 + ci * stride;                                  // chunk number inside the expert
-    const int g_c = c == nch - 1 ? last : G;                         // its groups
-    const int r2 = rem - ci * G * mtiles;                            // my tile inside the chunk
+    const int g_c = Gc + (c < big);                                  // its groups
+    const int r2 = rem - (ci <= bigmine ? ci * (Gc + 1) : in_big / mtiles + (ci - bigmine) * Gc) * mtiles;      // my tile inside the chunk
+    const int G0 = c * Gc + min(c, big);                             // its first group
     // Order inside a chunk.  Blocks are handed to compute units first come, first served, and a tall tile
     // takes longer than the others.  The tall tiles of all groups of the chunk come first, then the other
     // tiles group by group: the compute units that arrive first get the long tiles, those that arrive late
@@ -141,7 +144,7 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
         jj = r2 / mtiles;
         mt = r2 - jj * mtiles;
     }
-    t.nt = c * G + jj;
+    t.nt = G0 + jj;
     t.mt = mt;
     t.e = p.e_begin + src;
     const int q = rows / BM, r = rows - q * BM;
@@ -178,15 +181,25 @@ __device__ __forceinline__ const char* tile_address(const GemmParams& p, const i
     return p.pool + (int64_t)slot * p.page_bytes + (int64_t)within * p.tile_bytes;
 }
 
-// Grid size that covers every tile for any routing result.  Total tiles <= NT * M with M = R / BM + n_experts
-// (>= the sum over the experts of their row tiles).  Dealt in chunks, an XCD gets from an expert at most
-// ceil(chunks / 8) chunks, i.e. at most an eighth of that expert's tiles plus two chunks' worth; a chunk has at
-// most max(32, row tiles of the expert) tiles.
-inline int gemm_grid(int NT, int R, int BM, int n_experts) {
+// Grid size that covers every tile for any routing result.  M = R / BM + n_experts bounds the sum of the experts'
+// row tiles.  Dealing single groups round robin, an XCD gets at most ceil(NT / 8) groups of an expert: ceil(NT / 8) * M
+// tiles.  Dealt in chunks, an expert with m row tiles (G = min(8, max(1, chunk_tiles / m)) groups per chunk, nch =
+// ceil(NT / G) chunks of Gc = NT / nch groups, NT - Gc * nch of them one group more) gives an XCD at most
+// ceil(nch / 8) chunks, of which at most ceil(big / 8) are the bigger ones; the most that exceeds ceil(NT / 8) * m
+// for any m is added once per expert.  (Blocks beyond the tiles leave at once, but each still costs about a
+// microsecond of a compute unit: the bound is kept tight.)
+inline int gemm_grid(int NT, int R, int BM, int n_experts, int chunk_tiles = 32) {
     const int64_t M = R / BM + n_experts;
-    const int64_t per_xcd = ((int64_t)NT * M + 7) / 8 + 2 * (32 * (int64_t)n_experts + M);
-    const int64_t plain = 8 * (((int64_t)NT + 7) / 8) * M;            // single groups dealt round robin (chunked = 0), or no dealing at all
-    return (int)std::max(8 * per_xcd, plain);
+    const int64_t plain_groups = (NT + 7) / 8;
+    int64_t slack = 0;
+    for (int m = 1; m <= chunk_tiles; ++m) {
+        const int G = std::min(std::max(1, chunk_tiles / m), 8);
+        if (G == 1) continue;                                         // single groups: no more than ceil(NT / 8) * m
+        const int nch = (NT + G - 1) / G, Gc = NT / nch, big = NT - Gc * nch;
+        const int64_t mine = (nch + 7) / 8, bigmine = std::min<int64_t>((big + 7) / 8, mine);
+        slack = std::max(slack, (mine * Gc + bigmine) * m - plain_groups * m);
+    }
+    return (int)(8 * (plain_groups * M + slack * n_experts));
 }
 
 inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const FfnArgs& a) {
@@ -206,7 +219,10 @@ inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const 
     p.half_tiles = get_opt(OPT_HALF_TILES);
     p.tall_rows = (s.dtype == MOE_DTYPE_BF16 && get_opt(OPT_TALL_TILES)) ? 32 : 0;
     p.tall_first = get_opt(OPT_TALL_FIRST);
-    p.chunked = std::min(std::max(get_opt(OPT_CHUNKED), 0), 32);      // the grid bound assumes chunks of at most max(32, row tiles) tiles
+    // chunks only when the experts have more than half a row tile of rows on average: below that the launch streams
+    // the weights, single groups spread over the XCDs are the better order, and the grid needs no slack for chunks
+    const int64_t rows_each = (int64_t)s.T * s.k / std::max(1, a.e_end - a.e_begin);
+    p.chunked = rows_each > 128 ? std::min(std::max(get_opt(OPT_CHUNKED), 0), 32) : 0;
     p.stagger_ticks = get_opt(OPT_STAGGER_NS) / 10;
     p.stagger_mode = get_opt(OPT_STAGGER_MODE);
 }

@@ -126,11 +126,11 @@ int launch_expert_ffn_f32(const moe_shape& s, const Geom& g, const FfnArgs& a, h
     GemmParams p{};
     fill_common(p, s, g, a);
     fill_gate_up(p, s, g, a);
-    int rc = launch_mode<0>(p, gemm_grid(p.NT, R, BM, a.e_end - a.e_begin), st);
+    int rc = launch_mode<0>(p, gemm_grid(p.NT, R, BM, a.e_end - a.e_begin, p.chunked), st);
     if (rc != MOE_OK) return rc;
     if (a.mid_event) MOE_HIP_TRY(hipEventRecord(a.mid_event, st));
     fill_down(p, s, g, a);
-    return launch_mode<1>(p, gemm_grid(p.NT, R, BM, a.e_end - a.e_begin), st);
+    return launch_mode<1>(p, gemm_grid(p.NT, R, BM, a.e_end - a.e_begin, p.chunked), st);
 }
 
 int launch_expert_ffn(const moe_shape& s, const FfnArgs& a, hipStream_t st) {
