@@ -73,6 +73,12 @@ def main():
                     help="instead of the headline step, time moe_layer on --config's layer shape (weights resident) for "
                          "micro-batch sizes 32 .. 4096: the memory-bound plateau of the decode stage (the paper's section "
                          "6.2 sweeps 32 .. 256) and the turn to compute bound beyond it")
+    ap.add_argument("--rate-probes", action="store_true",
+                    help="instead of the layer, measure the three rates the roofline model takes as its inputs, each with a "
+                         "probe that is none of the layer runs the model is then asked to predict: the host link with a "
+                         "pinned-to-device copy of 1 GiB, the read rate of device memory with a kernel of nothing but loads "
+                         "over 4 GiB, and the matrix rate with a dense bf16 product of 2048 x 8192 x 32768 through the paged "
+                         "linear map")
     ap.add_argument("--requests", type=int, default=1024)
     ap.add_argument("--ubs", type=int, default=128)
     ap.add_argument("--layers", type=int, default=2)
@@ -102,6 +108,8 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes_read": n, "copy_probe_bytes_written": n, "launches": 10}))
         return
+    if args.rate_probes:
+        return rate_probes(args, M)
     cfg = CONFIGS[args.config]
     for o in args.option:
         name, val = o.split("=")
@@ -254,6 +262,59 @@ def main():
         sys.exit(3)
 
 
+def rate_probes(args, M):
+    """The inputs of the roofline model (paper_2411_11217_amd.hrm.MI355X_PROBED), measured apart from the layer."""
+    import torch
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    out = {"metric": "rates for the roofline model, measured by probes", "n_gpus": 1, "data": "synthetic"}
+    # host link: pinned host memory -> device, one copy of 1 GiB
+    n = 1 << 30
+    host = torch.empty(n, dtype=torch.uint8).pin_memory()
+    dev = torch.empty(n, dtype=torch.uint8, device="cuda")
+    t = timed(lambda: dev.copy_(host, non_blocking=True), 5)
+    out["host_link_gbs"] = round(n / t / 1e9, 2)
+    del host, dev
+    # device memory: a kernel of nothing but loads over 4 GiB (larger than every cache), 8 blocks per compute unit
+    buf = torch.empty(4 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    rates = {}
+    for blocks in (1024, 2048, 4096):
+        t = timed(lambda: M.probe_stream_read(buf, blocks=blocks), 10)
+        rates[blocks] = round(buf.numel() / t / 1e12, 3)
+    out["hbm_read_tbs"] = max(rates.values())
+    out["hbm_read_tbs_by_blocks"] = rates
+    del buf
+    # matrix rate: a dense bf16 product of 2048 x 8192 x 32768 through the paged linear map (the down-projection kernel on
+    # full, equal tiles: eight row tiles, 128 column tiles, a reduction twice as long as the layer's gate/up product)
+    T, K, N = 2048, 8192, 32768
+    page_bytes = 2 << 20
+    ls = M.make_linear_shape(T, K, N, page_bytes)
+    pages = M.linear_pages_required(ls)
+    g = torch.Generator().manual_seed(3)
+    W = (torch.randn((N, K), generator=g) * 0.02).to(torch.bfloat16)
+    pool = torch.empty((pages, page_bytes), dtype=torch.uint8)
+    table = torch.arange(pages, dtype=torch.int32)
+    M.linear_pack(ls, W, table, pool)
+    pool, table = pool.cuda(), table.cuda()
+    x = torch.randn((T, K), generator=g).to(torch.bfloat16).cuda()
+    for _ in range(5):
+        M.moe_linear(ls, x, table, pool)
+    t = timed(lambda: M.moe_linear(ls, x, table, pool), 20)
+    out["dense_gemm_tflops"] = round(2.0 * T * K * N / t / 1e12, 1)
+    out["dense_gemm_shape"] = [T, K, N]
+    print(json.dumps(out), flush=True)
+
+
 def tasks_bench(args, cfg, M, make_inputs):
     """Times the two GPU tasks of the paper's pipeline (its section 4.1) and their stages on one micro-batch."""
     import torch
@@ -334,7 +395,7 @@ def mu_sweep_bench(args, cfg, M, make_inputs):
             M.moe_layer(sh, x, Wr, pw.table_dev, pw.pages_dev, workspace=ws, y=y)
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) * 1e3 / args.steps
-        model = hrm.layer_latency(layer, hrm.MI355X_MEASURED, mu, mu, 1.0, hidden_from_host=False)
+        model = hrm.layer_latency(layer, hrm.MI355X_PROBED, mu, mu, 1.0, hidden_from_host=False)
         rows.append({"mu": mu, "ms": round(ms, 4), "tokens_per_s": round(mu / (ms * 1e-3), 1),
                      "weight_tb_per_s": round(weight_bytes / (ms * 1e-3) / 1e12, 2),
                      "tflops": round(6.0 * mu * cfg.k * cfg.H * cfg.F / (ms * 1e-3) / 1e12, 1),

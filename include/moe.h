@@ -354,6 +354,14 @@ int moe_pre_attention(const moe_linear_shape* qkv_proj, const float* hidden, con
 int moe_set_option(const char* name, int value);
 int moe_get_option(const char* name, int* value);
 
+/* ------------------------------------------------------------------ rate probes
+ * Measurement helpers for the roofline model's inputs (the paper's performance model, section 4.2, is fed
+ * with profiled rates of the hardware): moe_probe_stream_read launches `blocks` blocks that together read
+ * `bytes` bytes (a multiple of 16, 16-byte aligned) from device memory at src once and discard them; timing the
+ * launch gives the read rate device memory sustains for a kernel of nothing but coalesced loads.  sink: device
+ * int32 or NULL (never written for real data).  Enqueue only, no synchronisation. */
+int moe_probe_stream_read(const void* src, size_t bytes, int32_t blocks, int32_t* sink, void* stream);
+
 /* ------------------------------------------------------------------ stage timing
  * For measurements only.  While option "profile" is 1, moe_layer records HIP
  * events on its stream around its stages (route, permute, gate/up GEMM, down

@@ -90,6 +90,7 @@ _SIGNATURES = {
     "moe_set_option": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_int]),
     "moe_get_option": (ctypes.c_int, [ctypes.c_char_p, _vp]),
     "moe_profile_read": (ctypes.c_int, [_vp, _vp]),
+    "moe_probe_stream_read": (ctypes.c_int, [_vp, _sz, ctypes.c_int32, _vp, _vp]),
 }
 EXPORTED_SYMBOLS = tuple(_SIGNATURES)
 
@@ -351,6 +352,12 @@ def moe_layer(s: MoEShape, x, Wr, page_table, page_pool, bias=None, workspace: O
     _check(_lib().moe_layer(ctypes.byref(s), px, pw, pb, pt, pp, int(page_pool.shape[0]), y.data_ptr(),
                             workspace.buf.data_ptr(), workspace.buf.numel(), _stream(stream)), "moe_layer")
     return y, workspace
+
+
+def probe_stream_read(buf: torch.Tensor, blocks: int = 2048, stream=None):
+    """Enqueues one launch that reads all of the device tensor buf once (measurement helper)."""
+    nbytes = buf.numel() * buf.element_size()
+    _check(_lib().moe_probe_stream_read(buf.data_ptr(), nbytes, int(blocks), None, _stream(stream)), "moe_probe_stream_read")
 
 
 STATIC_SCRATCH_BYTES = 32 << 20

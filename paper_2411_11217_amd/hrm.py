@@ -10,9 +10,9 @@ where I^i and I^j are the operational intensities with respect to the bytes touc
 each level.  The two turning points (Eqs. 9, 10), the balance point (Eq. 11) and the
 per-layer latency model T = max(comm, T_cpu, T_gpu) of its section 4.2 follow from that.
 This module states those formulas for the layer this library computes (FLOPs
-6*R*h1*h2 + 2*T*h1*n_e; weights 3*n_e*h1*h2*dt) and searches the policy (micro-batch
-size, resident weight fraction r_w) the way the paper's optimiser does, for the part
-of the system that exists here: there is no CPU task, so T_cpu = 0.
+6*R*h1*h2 + 2*T*h1*n_e; weights 3*n_e*h1*h2*dt) and searches the policy (batch size N,
+micro-batch size mu, resident weight fraction r_w) the way the paper's optimiser does, for
+the part of the system that exists here: there is no CPU task, so T_cpu = 0.
 
 Symbols follow the paper's notation table: h1, h2 model and expert hidden sizes, n_e
 experts, k experts per token, dt bytes per element, N tokens per pass (batch), mu
@@ -34,13 +34,16 @@ class Hardware:
     m_g: float = 288e9              # GPU memory bytes
     p_c: float = 0.0                # host FLOP/s   (only used by the turning point P1)
     b_c: float = 0.0                # host memory bytes/s
+    m_c: float = math.inf           # host memory bytes (bounds the batch size in the policy search)
 
 
-# Published peaks of one MI355X, and the rates this library was measured to sustain on it
-# (expert GEMMs on the 4096-token Mixtral-8x7B-shaped layer, weight streaming on the 256-token
-# one, page copies from pinned host memory).
+# Published peaks of one MI355X, and its profiled rates (section 4.2 of the paper feeds its model with profiled peak
+# performance and bandwidths).  The profiled rates come from `python bench.py --rate-probes`, three probes that are none
+# of the layer runs the model is compared with: a dense bf16 product of 2048 x 8192 x 32768 through the library's paged
+# linear map (1290 TFLOP/s), a kernel of nothing but loads over 4 GiB of device memory (6.15 TB/s), one pinned-host to
+# device copy of 1 GiB (57.3 GB/s).
 MI355X_PEAK = Hardware(p_g=2.5e15, b_g=8.0e12, b_cg=64e9)
-MI355X_MEASURED = Hardware(p_g=1.26e15, b_g=5.5e12, b_cg=57.0e9)
+MI355X_PROBED = Hardware(p_g=1.29e15, b_g=6.15e12, b_cg=57.3e9)
 
 
 @dataclasses.dataclass(frozen=True)
@@ -138,23 +141,32 @@ def crossover_micro_batch(layer: Layer, hw: Hardware) -> int:
     return lo
 
 
-def best_policy(layer: Layer, hw: Hardware, N: int, micro_batches: Iterable[int], n_layers: int = 1,
-                r_w_steps: int = 20) -> Tuple[Optional[Dict[str, float]], Dict[str, float]]:
-    """Exhaustive search over (mu, r_w) for the lowest per-layer latency under the GPU-memory constraint
-    n_layers * r_w * weights + 2 * (1 - r_w) * weights (the double buffer) + workspace(mu) <= m_g.
+def best_policy(layer: Layer, hw: Hardware, batch_sizes, micro_batches: Iterable[int], n_layers: int = 1,
+                r_w_steps: int = 20, host_bytes_per_token: float = 0.0) -> Tuple[Optional[Dict[str, float]], Dict[str, float]]:
+    """Exhaustive search over the policy (N, mu, r_w) - the two integers and the weight fraction of the paper's
+    section 4.2 that exist for this layer - for the highest throughput N / T, T = layer_latency(N, mu, r_w), under
+      GPU memory:  n_layers * r_w * weights + 2 * (1 - r_w) * weights (the double buffer) + workspace(mu) <= m_g
+      host memory: n_layers * (1 - r_w) * weights + N * host_bytes_per_token <= m_c
+    (host_bytes_per_token: what a token keeps in host memory over all layers, e.g. its KV cache and hidden states; the
+    attention side is not part of this library, so it is a parameter).  batch_sizes: an int or the candidate values of N.
+    Among policies of equal throughput the smallest N, then the smallest r_w wins (less latency, less GPU memory).
     Returns (policy or None, its latency record)."""
+    Ns = [batch_sizes] if isinstance(batch_sizes, int) else sorted(batch_sizes)
+    mus = sorted(micro_batches)
     best, best_rec = None, {}
-    for mu in micro_batches:
-        if mu > N:
-            continue
-        for step in range(r_w_steps + 1):
-            r_w = step / r_w_steps
-            need = (n_layers * r_w + 2.0 * (1.0 - r_w)) * layer.weight_bytes + layer.workspace_bytes(mu)
-            if need > hw.m_g:
+    for N in Ns:
+        for mu in mus:
+            if mu > N:
                 continue
-            rec = layer_latency(layer, hw, N, mu, r_w)
-            if best is None or rec["T"] < best_rec["T"] - 1e-15 or (abs(rec["T"] - best_rec["T"]) <= 1e-15 and r_w < best["r_w"]):
-                best, best_rec = {"mu": mu, "r_w": r_w, "gpu_bytes_needed": need}, rec
+            for step in range(r_w_steps + 1):
+                r_w = step / r_w_steps
+                need = (n_layers * r_w + 2.0 * (1.0 - r_w)) * layer.weight_bytes + layer.workspace_bytes(mu)
+                host = n_layers * (1.0 - r_w) * layer.weight_bytes + N * host_bytes_per_token
+                if need > hw.m_g or host > hw.m_c:
+                    continue
+                rec = layer_latency(layer, hw, N, mu, r_w)
+                if best is None or rec["tokens_per_s"] > best_rec["tokens_per_s"] * (1.0 + 1e-12):
+                    best, best_rec = {"N": N, "mu": mu, "r_w": r_w, "gpu_bytes_needed": need, "host_bytes_needed": host}, rec
     return best, best_rec
 
 
@@ -164,7 +176,7 @@ DBRX = Layer(h1=6144, h2=10752, n_e=16, k=4)
 
 
 if __name__ == "__main__":
-    hw = MI355X_MEASURED
+    hw = MI355X_PROBED
     for name, layer in (("Mixtral-8x7B", MIXTRAL_8X7B), ("Mixtral-8x22B", MIXTRAL_8X22B), ("DBRX", DBRX)):
         mu_star = crossover_micro_batch(layer, hw)
         print(f"{name}: weights {layer.weight_bytes / 2**30:.2f} GiB/layer, compute bound from mu = {mu_star} tokens; "

@@ -46,7 +46,7 @@ def test_layer_counts():
 
 
 def test_latency_model_properties():
-    L, hw = hrm.DBRX, hrm.MI355X_MEASURED
+    L, hw = hrm.DBRX, hrm.MI355X_PROBED
     prev = None
     for step in range(11):
         r = hrm.layer_latency(L, hw, 16384, 4096, step / 10)
@@ -67,7 +67,7 @@ def test_latency_model_properties():
 
 
 def test_crossover_micro_batch_is_the_ridge():
-    L, hw = hrm.MIXTRAL_8X7B, hrm.MI355X_MEASURED
+    L, hw = hrm.MIXTRAL_8X7B, hrm.MI355X_PROBED
     mu = hrm.crossover_micro_batch(L, hw)
     assert L.flops(mu) / hw.p_g >= L.gpu_bytes(mu) / hw.b_g
     assert L.flops(mu - 1) / hw.p_g < L.gpu_bytes(mu - 1) / hw.b_g
@@ -78,23 +78,30 @@ def test_crossover_micro_batch_is_the_ridge():
     assert 256 < mu < 4096
 
 
-# (layer, N, mu, r_w, hidden states cross the link, measured ms per layer on one MI355X, tolerance):
-# bench.py (inputs resident) and bench.py --pipeline (hidden states copied from the host)
+# (layer, N, mu, r_w, hidden states cross the link, measured ms per layer on one MI355X): bench.py (inputs resident)
+# and bench.py --pipeline (hidden states copied from the host).  The model's rates are NOT fitted to these runs: they
+# come from three probes (bench.py --rate-probes: a dense product, a load-only kernel, one pinned-host copy), so the
+# comparison says how far the layer is from what the probes promise.
 MEASURED = [
-    (hrm.MIXTRAL_8X7B, 256, 256, 1.0, False, 0.53, 0.05),
-    (hrm.MIXTRAL_8X7B, 4096, 4096, 1.0, False, 2.24, 0.05),
-    (hrm.MIXTRAL_8X22B, 8192, 8192, 1.0, False, 7.48, 0.08),
-    (hrm.DBRX, 16384, 4096, 0.0, True, 115.3, 0.03),
-    (hrm.DBRX, 16384, 4096, 48 / 95, True, 59.0, 0.03),
-    (hrm.DBRX, 16384, 4096, 76 / 95, True, 26.2, 0.03),     # next to the turning point: link time = 1.25 x GPU time
-    (hrm.DBRX, 16384, 4096, 1.0, True, 21.9, 0.08),
+    (hrm.MIXTRAL_8X7B, 256, 256, 1.0, False, 0.53),          # weight streaming: 1.14 x the model (the load-only rate is not reached)
+    (hrm.MIXTRAL_8X7B, 1024, 1024, 1.0, False, 0.73),        # at the ridge: 1.31 x (one row tile per expert, both bounds bite)
+    (hrm.MIXTRAL_8X7B, 4096, 4096, 1.0, False, 2.13),        # compute bound: 0.95 x (the ragged layer beats the dense probe's rate)
+    (hrm.MIXTRAL_8X22B, 8192, 8192, 1.0, False, 7.48),
+    (hrm.DBRX, 16384, 4096, 0.0, True, 115.3),               # link bound
+    (hrm.DBRX, 16384, 4096, 48 / 95, True, 59.0),
+    (hrm.DBRX, 16384, 4096, 76 / 95, True, 26.2),            # next to the turning point: link time = 1.25 x GPU time
+    (hrm.DBRX, 16384, 4096, 1.0, True, 21.9),
 ]
 
 
-@pytest.mark.parametrize("layer,N,mu,r_w,hidden,measured_ms,tol", MEASURED)
-def test_model_with_measured_rates_predicts_the_measured_latency(layer, N, mu, r_w, hidden, measured_ms, tol):
-    r = hrm.layer_latency(layer, hrm.MI355X_MEASURED, N, mu, r_w, hidden_from_host=hidden)
-    assert r["T"] * 1e3 == pytest.approx(measured_ms, rel=tol)
+@pytest.mark.parametrize("layer,N,mu,r_w,hidden,measured_ms", MEASURED)
+def test_model_with_probed_rates_brackets_the_measured_latency(layer, N, mu, r_w, hidden, measured_ms):
+    r = hrm.layer_latency(layer, hrm.MI355X_PROBED, N, mu, r_w, hidden_from_host=hidden)
+    ratio = measured_ms / (r["T"] * 1e3)
+    # link- and compute-bound runs within a few percent of the model, the streaming run within 16 %; the ridge is the
+    # known weak spot (a 256-row tile is the unit of work there)
+    lo, hi = (0.93, 1.35) if N == 1024 else (0.93, 1.16)
+    assert lo <= ratio <= hi, ratio
     # and the nominal peaks are an upper bound on what was measured
     assert hrm.layer_latency(layer, hrm.MI355X_PEAK, N, mu, r_w, hidden_from_host=hidden)["T"] * 1e3 < measured_ms
 
@@ -102,9 +109,9 @@ def test_model_with_measured_rates_predicts_the_measured_latency(layer, N, mu, r
 def test_policy_search_respects_memory_and_finds_the_balance():
     L = hrm.DBRX
     # plenty of GPU memory: compute bound, with the smallest resident fraction that gets there
-    pol, rec = hrm.best_policy(L, hrm.MI355X_MEASURED, 16384, [1024, 4096], n_layers=40)
-    assert rec["bound"] == "gpu" and pol["r_w"] == pytest.approx(0.85)
-    assert hrm.layer_latency(L, hrm.MI355X_MEASURED, 16384, pol["mu"], 0.80)["bound"] == "link"
+    pol, rec = hrm.best_policy(L, hrm.MI355X_PROBED, 16384, [1024, 4096], n_layers=40)
+    assert rec["bound"] == "gpu" and pol["N"] == 16384
+    assert hrm.layer_latency(L, hrm.MI355X_PROBED, 16384, pol["mu"], pol["r_w"] - 0.05)["bound"] == "link"
     # 96 GB for 40 layers (236 GiB of weights): only part fits; the search keeps as much resident as fits
     small = hrm.Hardware(p_g=1.05e15, b_g=5.0e12, b_cg=55.7e9, m_g=96e9)
     pol, rec = hrm.best_policy(L, small, 16384, [1024, 4096], n_layers=40)
@@ -115,3 +122,52 @@ def test_policy_search_respects_memory_and_finds_the_balance():
     # nothing fits: no policy
     none, _ = hrm.best_policy(L, hrm.Hardware(1e15, 5e12, 55e9, m_g=1e9), 16384, [4096])
     assert none is None
+
+
+def test_policy_search_over_the_batch_size():
+    """N is one of the policy's two integers (section 4.2): a larger batch amortises the weights that cross the link,
+    until the layer is compute bound or host memory is full."""
+    L = hrm.DBRX
+    Ns = [1024, 2048, 4096, 8192, 16384, 32768, 65536]
+    mus = [256, 1024, 4096]
+    # weights streamed (tiny GPU): throughput grows with N while the link bounds the layer, so the largest N that host
+    # memory allows wins
+    tiny = hrm.Hardware(p_g=1.29e15, b_g=6.15e12, b_cg=57.3e9, m_g=40e9, m_c=float("inf"))
+    pol, rec = hrm.best_policy(L, tiny, Ns, mus, n_layers=40)
+    assert pol["N"] == 65536 and rec["bound"] == "link"
+    by_n = [hrm.best_policy(L, tiny, N, mus, n_layers=40)[1]["tokens_per_s"] for N in Ns]
+    assert all(b > a for a, b in zip(by_n, by_n[1:]))
+    # a host-memory limit caps the batch: 1 MiB per token over all layers and 250 GB of host memory beside the
+    # host's share of the weights
+    pol_c, rec_c = hrm.best_policy(L, dataclass_replace(tiny, m_c=40 * L.weight_bytes + 20e9), Ns, mus, n_layers=40,
+                                   host_bytes_per_token=1 << 20)
+    m_c = 40 * L.weight_bytes + 20e9
+    assert pol_c["N"] == 32768 and pol_c["host_bytes_needed"] <= m_c          # 65536 tokens would need 69 GB beside the weights
+    assert all(40 * (1 - q / 20) * L.weight_bytes + 65536 * (1 << 20) > m_c or
+               (40 * q / 20 + 2 * (1 - q / 20)) * L.weight_bytes > tiny.m_g for q in range(21))
+    assert rec_c["tokens_per_s"] < rec["tokens_per_s"]
+    # everything resident: once a micro-batch is compute bound a larger N buys nothing, and the smallest such N is kept
+    big = hrm.MI355X_PROBED
+    pol_r, rec_r = hrm.best_policy(hrm.MIXTRAL_8X7B, big, Ns, [4096], n_layers=1)
+    assert pol_r["r_w"] == 1.0 or rec_r["bound"] == "gpu"
+    assert pol_r["N"] == 4096
+    # brute force over the same grid agrees
+    best = None
+    for N in Ns:
+        for mu in mus:
+            if mu > N:
+                continue
+            for step in range(21):
+                r_w = step / 20
+                need = (40 * r_w + 2 * (1 - r_w)) * L.weight_bytes + L.workspace_bytes(mu)
+                if need > tiny.m_g:
+                    continue
+                t = hrm.layer_latency(L, tiny, N, mu, r_w)["tokens_per_s"]
+                if best is None or t > best[0] * (1 + 1e-12):
+                    best = (t, N, mu, r_w)
+    assert (pol["N"], pol["mu"], pol["r_w"]) == best[1:]
+
+
+def dataclass_replace(hw, **kw):
+    import dataclasses
+    return dataclasses.replace(hw, **kw)
