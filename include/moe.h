@@ -348,6 +348,10 @@ int moe_pre_attention(const moe_linear_shape* qkv_proj, const float* hidden, con
  *                 remainder of an expert's rows needs no tile of its own.        default 1
  *   "fuse_gather" 1: moe_layer's bf16 gate/up GEMM gathers the rows of x itself (no
  *                 x_perm copy).                                              default 1
+ *   "chunked"     tile order of the expert GEMMs: the column tiles of an expert go to the XCDs
+ *                 in chunks of about this many tiles (at most 32); 0: one by one.  default 32
+ *   "tall_first"  1: inside a chunk the tall row tiles are numbered first.       default 1
+ *   "stagger_ns", "stagger_mode"  experiments with late starts of the first blocks.  default 0
  *   "profile"     1: moe_layer records stage events (see below).  Setting it to 1 creates
  *                 the events (the only option whose setter touches the device; it may
  *                 return MOE_ERR_HIP); the layer calls themselves create nothing.  default 0 */

@@ -168,6 +168,65 @@ __device__ __forceinline__ void mfma_16x16x32_v(f32x4& acc, const i32x4& a, cons
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
 #endif
 }
+// The MFMAs of a tall tile's extra row tile, all in ONE statement: acc[j] += a * b[j] for the column fragments that
+// `which` selects - 0: all of them; 1 / 2: the first / second half of a split (see the kernel), i.e. with GATE_UP the
+// gate fragments 0, 1 (2, 3) and their up fragments 4, 5 (6, 7), else fragments 0 .. NJ/2-1 (NJ/2 .. NJ-1).  The choice
+// is a branch INSIDE the statement: the compiler sees one unconditional read-modify-write of all accumulator tiles and
+// has no control flow to merge them across (with a branch in the source it copied the tiles next to the MFMAs that
+// were still writing them).
+template <bool GATE_UP>
+__device__ __forceinline__ void mfma_extra_tile_8(f32x4 (&acc)[8], const i32x4& a, const i32x4 (&b)[8], int which) {
+#ifdef __HIP_DEVICE_COMPILE__
+#define MOE_XM(J) "v_mfma_f32_16x16x32_bf16 %" #J ", %8, %" MOE_XB_##J ", %" #J "\n\t"
+#define MOE_XB_0 "9"
+#define MOE_XB_1 "10"
+#define MOE_XB_2 "11"
+#define MOE_XB_3 "12"
+#define MOE_XB_4 "13"
+#define MOE_XB_5 "14"
+#define MOE_XB_6 "15"
+#define MOE_XB_7 "16"
+    if constexpr (GATE_UP) {
+        asm volatile("s_cmp_lg_u32 %17, 0\n\ts_cbranch_scc1 1f\n\t"
+                     MOE_XM(0) MOE_XM(1) MOE_XM(2) MOE_XM(3) MOE_XM(4) MOE_XM(5) MOE_XM(6) MOE_XM(7)
+                     "s_branch 3f\n1:\n\ts_cmp_lg_u32 %17, 1\n\ts_cbranch_scc1 2f\n\t"
+                     MOE_XM(0) MOE_XM(1) MOE_XM(4) MOE_XM(5)
+                     "s_branch 3f\n2:\n\t"
+                     MOE_XM(2) MOE_XM(3) MOE_XM(6) MOE_XM(7)
+                     "3:\n\t"
+                     : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "+v"(acc[4]), "+v"(acc[5]), "+v"(acc[6]), "+v"(acc[7])
+                     : "v"(a), "v"(b[0]), "v"(b[1]), "v"(b[2]), "v"(b[3]), "v"(b[4]), "v"(b[5]), "v"(b[6]), "v"(b[7]), "s"(which)
+                     : "scc");
+    } else {
+        asm volatile("s_cmp_lg_u32 %17, 0\n\ts_cbranch_scc1 1f\n\t"
+                     MOE_XM(0) MOE_XM(1) MOE_XM(2) MOE_XM(3) MOE_XM(4) MOE_XM(5) MOE_XM(6) MOE_XM(7)
+                     "s_branch 3f\n1:\n\ts_cmp_lg_u32 %17, 1\n\ts_cbranch_scc1 2f\n\t"
+                     MOE_XM(0) MOE_XM(1) MOE_XM(2) MOE_XM(3)
+                     "s_branch 3f\n2:\n\t"
+                     MOE_XM(4) MOE_XM(5) MOE_XM(6) MOE_XM(7)
+                     "3:\n\t"
+                     : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "+v"(acc[4]), "+v"(acc[5]), "+v"(acc[6]), "+v"(acc[7])
+                     : "v"(a), "v"(b[0]), "v"(b[1]), "v"(b[2]), "v"(b[3]), "v"(b[4]), "v"(b[5]), "v"(b[6]), "v"(b[7]), "s"(which)
+                     : "scc");
+    }
+#endif
+}
+// the same for the narrow block's four column fragments (down projection only): halves 0, 1 and 2, 3
+__device__ __forceinline__ void mfma_extra_tile_4(f32x4 (&acc)[4], const i32x4& a, const i32x4 (&b)[4], int which) {
+#ifdef __HIP_DEVICE_COMPILE__
+#define MOE_YM(J, B) "v_mfma_f32_16x16x32_bf16 %" #J ", %4, %" #B ", %" #J "\n\t"
+    asm volatile("s_cmp_lg_u32 %9, 0\n\ts_cbranch_scc1 1f\n\t"
+                 MOE_YM(0, 5) MOE_YM(1, 6) MOE_YM(2, 7) MOE_YM(3, 8)
+                 "s_branch 3f\n1:\n\ts_cmp_lg_u32 %9, 1\n\ts_cbranch_scc1 2f\n\t"
+                 MOE_YM(0, 5) MOE_YM(1, 6)
+                 "s_branch 3f\n2:\n\t"
+                 MOE_YM(2, 7) MOE_YM(3, 8)
+                 "3:\n\t"
+                 : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])
+                 : "v"(a), "v"(b[0]), "v"(b[1]), "v"(b[2]), "v"(b[3]), "s"(which)
+                 : "scc");
+#endif
+}
 __device__ __forceinline__ void load_vgpr_16(i32x4& dst, const char* ptr) {
 #ifdef __HIP_DEVICE_COMPILE__
     asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(ptr) : "memory");
@@ -236,7 +295,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
 #ifdef MOE_TIMELINE
     long long* tl = g_timeline + ((size_t)MODE * 8192 + (blockIdx.x & 8191)) * 24;
     int tli = 1;
-    if (tid == 0) tl[0] = ((long long)e << 40) | ((long long)tc.mt << 24) | (long long)nt;
+    if (tid == 0) tl[0] = ((long long)rows_here << 48) | ((long long)e << 40) | ((long long)tc.mt << 24) | (long long)nt;
     MOE_TL_STAMP();
 #endif
     if (p.stagger_ticks > 0 && (blockIdx.x >> 3) < 32) {       // the first block of a compute unit
@@ -281,14 +340,28 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         w.tile = page_addr(w.page) + (int64_t)w.within * 16384;
         return w;
     };
-    auto walk_next = [&](TileWalk& w) __attribute__((always_inline)) {
-        w.tile += 16384;
-        if (++w.within == p.tpp) {
-            w.within = 0;
-            w.tile = page_addr(++w.page);
+    TileWalk w0 = walk_start(pt0 * p.KT), w1 = walk_start(pt1 * p.KT);
+    // Both walks one tile on.  ONE test for the rare page boundary, marked unlikely so that the look-up sits out of line
+    // and the common path falls through: with one wavefront per SIMD every taken branch is some 30 cycles without an
+    // MFMA, and a test per walk that jumps over its look-up cost two of them per k-step (2.4 % of the loop).
+    auto walk_next_both = [&]() __attribute__((always_inline)) {
+        w0.tile += 16384;
+        ++w0.within;
+        if (NB == 2) {
+            w1.tile += 16384;
+            ++w1.within;
+        }
+        if (__builtin_expect((w0.within == p.tpp) | (NB == 2 && w1.within == p.tpp), 0)) {
+            if (w0.within == p.tpp) {
+                w0.within = 0;
+                w0.tile = page_addr(++w0.page);
+            }
+            if (NB == 2 && w1.within == p.tpp) {
+                w1.within = 0;
+                w1.tile = page_addr(++w1.page);
+            }
         }
     };
-    TileWalk w0 = walk_start(pt0 * p.KT), w1 = walk_start(pt1 * p.KT);
 
     // ---- sources of the global -> LDS loads: a wave-uniform base that moves along k plus a 32-bit
     // offset per lane that never changes, so a half-step costs a few scalar additions ----------------
@@ -317,8 +390,15 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     // it must never have a reason to copy them.  Any control flow around their uses makes it merge values with
     // register copies next to the asm statements, which then read registers still being written (seen as wrong
     // extra rows when the MFMAs of this block were put under a branch on the number of extra rows).  So: one
-    // unconditional sequence per half-step under the single test of `extra`, nothing else.
+    // unconditional sequence per half-step under the single test of `extra`; what varies with the number of extra
+    // rows is decided inside the asm statement (mfma_extra_tile_8 / _4).
     const int extra = rows_here > BM ? rows_here - BM : 0;
+    // At most 16 extra rows: ONE extra 16-row MFMA tile, rows BM .. BM + 15, and the two wavefront rows - which hold the
+    // same column fragments - take half of the column fragments each (half the extra MFMAs per wavefront).  extra_which:
+    // 0 = every fragment (more than 16 extra rows: wavefront row wm has the rows BM + 16 wm ..), 1 / 2 = this
+    // wavefront row's half.
+    const bool split_extra = extra > 0 && extra <= 16;
+    const int extra_which = __builtin_amdgcn_readfirstlane(split_extra ? 1 + wm : 0);
     const char* ae_ptr = p.A;
     i32x4 AE[4];
     f32x4 accE[NJ];
@@ -327,7 +407,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) AE[u] = i32x4{0, 0, 0, 0};
     if (extra) {
-        const int er = min(BM + wm * 16 + (lane & 15), rows_here - 1);
+        const int er = min(BM + (split_extra ? 0 : wm * 16) + (lane & 15), rows_here - 1);
         const int64_t src = p.a_gather ? (int64_t)min(max(p.a_gather[row0 + er] / p.a_div, 0), p.a_rows - 1) : (int64_t)row0 + er;
         ae_ptr = p.A + src * p.lda_bytes + (lane >> 4) * 16;      // + 64 bytes per half-step
     }
@@ -353,10 +433,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         }
     };
     auto advance_b = [&](int kn, int odd, int i) __attribute__((always_inline)) {
-        if (i == 2 * NB - 1 && odd && kn + 1 < KH) {
-            walk_next(w0);
-            if (NB == 2) walk_next(w1);
-        }
+        if (i == 2 * NB - 1 && odd && kn + 1 < KH) walk_next_both();
     };
     // the loads of the prologue (no MFMA to pair them with)
     auto load_a = [&](int part, int i) __attribute__((always_inline)) {
@@ -438,9 +515,16 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     // be in flight when the stages of half-step k must be complete (those issued during the two
     // half-steps before).  Weight fragment set U & 1 belongs to half-step k: S is even, so the parity of
     // k is static too.
-    auto main_loop = [&](auto half_tile_c, auto rt_c, auto na_c) __attribute__((always_inline)) {
+    // TALL: the loop of a tall tile (full loop only).  A copy of the loop of its own rather than a test of `extra` in
+    // every half-step: with one wavefront per SIMD a taken branch costs some 30 cycles of an idle matrix core, and the
+    // test cost two of them (to the block and back) plus the branch around its load: measured per half-step about as
+    // much as the eight extra MFMAs themselves (a tall tile took 15 % longer than a full one for 12.5 % more MFMAs with
+    // the extra tile's loads taken out, and still 15 % longer with half the extra MFMAs).
+    auto main_loop = [&](auto half_tile_c, auto rt_c, auto na_c, auto tall_c) __attribute__((always_inline)) {
         using std::integral_constant;
         constexpr bool HALF = decltype(half_tile_c)::value;
+        constexpr bool TALL = decltype(tall_c)::value;
+        static_assert(!(HALF && TALL), "tall tiles run the full loop");
         constexpr int RT = decltype(rt_c)::value;       // short tiles: row tiles a wavefront computes (4, 2)
         constexpr int NA = decltype(na_c)::value;       // short tiles: activation load instructions per k-step (4, 2, 1: 32 rows each)
         constexpr int WROWS = HALF ? 64 : 128;          // rows of a wavefront
@@ -495,12 +579,16 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                         MOE_FENCE();
                     }
                 });
-                if (__builtin_expect(extra != 0, 0)) {       // tall tile: the extra row tile against the column fragments of k
-#pragma unroll
-                    for (int jj = 0; jj < NJ; ++jj) mfma_16x16x32_v(accE[jj], AE[U], BF[HP][jj]);
+                if constexpr (TALL) {                        // tall tile: the extra row tile against the column fragments of k
+                    if constexpr (NJ == 8) mfma_extra_tile_8<MODE == 0>(accE, AE[U], BF[HP], extra_which);
+                    else mfma_extra_tile_4(accE, AE[U], BF[HP], extra_which);
                     MOE_FENCE();
-                    if (k + 4 < KH) load_vgpr_16(AE[U], ae_ptr + (int64_t)(k + 4) * 64);
+#ifndef MOE_TALL_NOLOAD      // (timing experiment only: the extra tile without its loads)
+                    // the fragment of half-step k + 4: there is one exactly while the activation loads go on (the last four
+                    // half-steps run without LA), so no test of k is needed
+                    if constexpr (LA) load_vgpr_16(AE[U], ae_ptr + (int64_t)(k + 4) * 64);
                     MOE_FENCE();
+#endif
                 }
             } else if (wact) {
                 constexpr int NH = NJ / 2, NG = RT * NH;            // column fragments and MFMAs of a group
@@ -562,7 +650,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         const std::false_type N{};
         // prologue, in the order the half-steps -4 .. -1 would have issued them: activation k-steps
         // 0 and 1, weight half-steps 0 .. 2 (KH is a multiple of 4 and at least 4)
-        if (!HALF && extra) {             // the oldest loads of the tile: complete at the first wait
+        if constexpr (TALL) {             // the oldest loads of the tile: complete at the first wait
 #pragma unroll
             for (int u = 0; u < 4; ++u) load_vgpr_16(AE[u], ae_ptr + u * 64);
         }
@@ -621,10 +709,11 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     // alone (the other wavefronts only load); at most 32: two row tiles instead of four.
     const bool half_tile = p.half_tiles && rows_here <= 128;
     using std::integral_constant;
-    if (!half_tile) main_loop(std::false_type{}, integral_constant<int, 4>{}, integral_constant<int, 4>{});
-    else if (rows_here > 64) main_loop(std::true_type{}, integral_constant<int, 4>{}, integral_constant<int, 4>{});
-    else if (rows_here > 32) main_loop(std::true_type{}, integral_constant<int, 4>{}, integral_constant<int, 2>{});
-    else main_loop(std::true_type{}, integral_constant<int, 2>{}, integral_constant<int, 1>{});
+    if (!half_tile && extra) main_loop(std::false_type{}, integral_constant<int, 4>{}, integral_constant<int, 4>{}, std::true_type{});
+    else if (!half_tile) main_loop(std::false_type{}, integral_constant<int, 4>{}, integral_constant<int, 4>{}, std::false_type{});
+    else if (rows_here > 64) main_loop(std::true_type{}, integral_constant<int, 4>{}, integral_constant<int, 4>{}, std::false_type{});
+    else if (rows_here > 32) main_loop(std::true_type{}, integral_constant<int, 4>{}, integral_constant<int, 2>{}, std::false_type{});
+    else main_loop(std::true_type{}, integral_constant<int, 2>{}, integral_constant<int, 1>{}, std::false_type{});
     const bool wact = !half_tile || wm == 0 || rows_here > 64;        // this wavefront has rows
     const int row_tiles = !half_tile ? 8 : (rows_here > 32 ? 4 : 2);   // and this many row tiles
 
@@ -669,11 +758,12 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         if (extra) {                           // the extra row tile of a tall tile
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int row = BM + wm * 16 + (lane >> 4) * 4 + r;
+                const int row = BM + (split_extra ? 0 : wm * 16) + (lane >> 4) * 4 + r;
                 if (row < rows_here) {
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        h[(int64_t)row * p.ldo + j * 16] = (__bf16)silu_mul(accE[j][r], accE[j + 4][r]);
+                        if (!split_extra || (j >> 1) == wm)          // split: this wavefront row's gate fragments only
+                            h[(int64_t)row * p.ldo + j * 16] = (__bf16)silu_mul(accE[j][r], accE[j + 4][r]);
                 }
             }
         }
@@ -712,11 +802,12 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
             if (extra) {                       // the extra row tile of a tall tile
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int row = BM + wm * 16 + (lane >> 4) * 4 + r;
+                    const int row = BM + (split_extra ? 0 : wm * 16) + (lane >> 4) * 4 + r;
                     if (row < rows_here) {
                         const float wr = sw[row];
 #pragma unroll
-                        for (int j = 0; j < NJ; ++j) o[(int64_t)row * p.ldo + j * 16] = accE[j][r] * wr;
+                        for (int j = 0; j < NJ; ++j)
+                            if (!split_extra || j / (NJ / 2) == wm) o[(int64_t)row * p.ldo + j * 16] = accE[j][r] * wr;      // split: this wavefront row's half
                     }
                 }
             }

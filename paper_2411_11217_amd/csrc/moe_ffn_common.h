@@ -71,6 +71,14 @@ __device__ __forceinline__ int lane_prefix_sum(int v, int lane) {
     return v;
 }
 
+// Tall tiles that take a remainder of r rows along with q full tiles (0 < r <= tall_rows * q).  A tall tile with at
+// most 16 extra rows costs half as many extra MFMAs as one with 17 .. 32 (bf16 kernel), so the remainder goes to
+// ceil(r / 16) tiles when there are that many, else to as few tiles as possible (ceil(r / tall_rows)).
+__device__ __forceinline__ int tall_tiles_of(int r, int q, int tall_rows) {
+    const int m16 = (r + 15) / 16;
+    return m16 <= q ? m16 : (r + tall_rows - 1) / tall_rows;
+}
+
 template <int BM>
 __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     TileCoord t{};
@@ -86,13 +94,12 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     const int x = p.xcd_remap ? (int)(blockIdx.x & 7) : 0;           // my chunks: those whose number is x modulo stride
     const int idx = p.xcd_remap ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;    // my position among their tiles
     // row tiles of my lane's expert.  q full tiles and a remainder r: when r <= tall_rows * q the remainder is
-    // spread over the last ceil(r / tall_rows) of the q tiles (each at most BM + tall_rows rows high: as few
-    // tall tiles as possible, every one costs an extra 16-row MFMA tile per wavefront), otherwise it is a tile
-    // of its own
+    // spread over the last tall_tiles_of(r, q) of the q tiles (each at most BM + tall_rows rows high), otherwise it is
+    // a tile of its own
     const int q_l = cnt / BM, r_l = cnt - q_l * BM;
     const bool rides_l = q_l >= 1 && r_l > 0 && r_l <= p.tall_rows * q_l;
     const int mtiles_l = rides_l ? q_l : q_l + (r_l > 0);
-    const int tall_l = rides_l ? (r_l + p.tall_rows - 1) / p.tall_rows : 0;
+    const int tall_l = rides_l ? tall_tiles_of(r_l, q_l, p.tall_rows) : 0;
     // chunks of my lane's expert: nch_l = ceil(NT / G) of them, of Gc_l or Gc_l + 1 groups each (the first big_l ones are
     // the bigger: equal sizes keep the XCDs' shares equal when the groups do not divide); an expert without rows has none
     const int G_l = (p.chunked && cnt > BM / 2) ? min(max(1, p.chunked / max(mtiles_l, 1)), 8) : 1;      // p.chunked: tiles a chunk aims at (32); at most 8 groups
@@ -150,7 +157,7 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     const int q = rows / BM, r = rows - q * BM;
     if (r > 0 && q >= 1 && r <= p.tall_rows * q) {
         // the last m tiles are BM + r / m rows high, the first r % m of them one row more
-        const int m = (r + p.tall_rows - 1) / p.tall_rows, plain = q - m;
+        const int m = tall_tiles_of(r, q, p.tall_rows), plain = q - m;
         const int i = t.mt - plain;
         if (i < 0) {
             t.row0 = seg + t.mt * BM;

@@ -26,12 +26,15 @@ ROW_TILE, TALL = 256, 32
 def row_tiles(n):
     """(first row, rows) of the row tiles the expert GEMMs cut a segment of n rows into, as include/moe.h documents it
     for the option "tall_tiles": q full tiles of 256 rows and a remainder r; when 0 < r <= 32 q the remainder rides along
-    with the last m = ceil(r / 32) tiles (each 256 + r / m rows high, the first r % m of them one more); otherwise it is
-    a tile of its own.  Only used to aim the sample, never to compute a value."""
+    with the last m tiles (each 256 + r / m rows high, the first r % m of them one more), m = ceil(r / 16) if there are
+    that many tiles, else ceil(r / 32); otherwise it is a tile of its own.  Only used to aim the sample, never to
+    compute a value."""
     q, r = divmod(n, ROW_TILE)
     if not M.get_option("tall_tiles") or q == 0 or r == 0 or r > TALL * q:
         return [(a, min(ROW_TILE, n - a)) for a in range(0, n, ROW_TILE)]
-    m = (r + TALL - 1) // TALL
+    m = (r + 15) // 16
+    if m > q:
+        m = (r + TALL - 1) // TALL
     base, more = ROW_TILE + r // m, r % m
     tiles = [(i * ROW_TILE, ROW_TILE) for i in range(q - m)]
     a = (q - m) * ROW_TILE
