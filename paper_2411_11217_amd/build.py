@@ -22,8 +22,12 @@ FLAGS = [
 ]
 
 
+HOST_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-pthread", "-Wall", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+
+
 def sources():
-    return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+    """The .hip files (device code, compiled by hipcc) and the .cpp files (host only, compiled by the host compiler)."""
+    return sorted(glob.glob(os.path.join(CSRC, "*.hip"))) + sorted(glob.glob(os.path.join(CSRC, "*.cpp")))
 
 
 def is_stale() -> bool:
@@ -46,10 +50,13 @@ def build(force: bool = True, verbose: bool = False, extra_flags=(), out: str = 
 
     def compile_one(src):
         obj = os.path.join(build_dir, os.path.basename(src)[:-4] + ".o")
-        cmd = [hipcc] + FLAGS + list(extra_flags) + ["-c", src, "-o", obj]
+        if src.endswith(".cpp"):
+            cmd = [os.environ.get("CXX", "g++")] + HOST_FLAGS + ["-c", src, "-o", obj]
+        else:
+            cmd = [hipcc] + FLAGS + list(extra_flags) + ["-c", src, "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
-            raise RuntimeError("hipcc failed for %s:\n%s" % (src, r.stderr[-8000:]))
+            raise RuntimeError("compiler failed for %s:\n%s" % (src, r.stderr[-8000:]))
         if verbose and r.stderr.strip():
             sys.stderr.write(r.stderr)
         return obj

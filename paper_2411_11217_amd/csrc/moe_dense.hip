@@ -17,22 +17,6 @@ using namespace moe;
 
 namespace {
 
-int validate_linear(const moe_linear_shape* s) {
-    if (!s) return MOE_ERR_INVALID_ARG;
-    if (s->dtype != MOE_DTYPE_BF16) return MOE_ERR_UNSUPPORTED_DTYPE;
-    if (s->T < 0 || s->K < 128 || s->N < 128 || s->K % 128 != 0 || s->N % kTileN != 0) return MOE_ERR_INVALID_ARG;
-    if ((int64_t)s->T > 0x3fffffff) return MOE_ERR_INVALID_ARG;
-    const int64_t tile = (int64_t)kTileN * kTileK * 2;
-    if (s->page_bytes <= 0 || s->page_bytes % tile != 0) return MOE_ERR_INVALID_ARG;
-    return MOE_OK;
-}
-
-int64_t linear_pages(const moe_linear_shape& s) {
-    const int64_t tiles = (int64_t)(s.N / kTileN) * (s.K / kTileK);
-    const int64_t tpp = s.page_bytes / ((int64_t)kTileN * kTileK * 2);
-    return (tiles + tpp - 1) / tpp;
-}
-
 __global__ void set_bounds_kernel(int32_t* offsets, int32_t T) {
     if (threadIdx.x == 0) {
         offsets[0] = 0;
@@ -122,38 +106,6 @@ int enqueue_add_rmsnorm(int32_t T, int32_t H, const float* hidden, const float* 
 }  // namespace
 
 extern "C" {
-
-int moe_linear_pages_required(const moe_linear_shape* s, int64_t* pages) {
-    int rc = validate_linear(s);
-    if (rc != MOE_OK) return rc;
-    if (!pages) return MOE_ERR_INVALID_ARG;
-    *pages = linear_pages(*s);
-    return MOE_OK;
-}
-
-int moe_linear_pack(const moe_linear_shape* s, const void* W, const int32_t* page_table, int64_t pool_pages,
-                    void* pages_out) {
-    int rc = validate_linear(s);
-    if (rc != MOE_OK) return rc;
-    if (!W || !page_table || !pages_out || pool_pages <= 0) return MOE_ERR_INVALID_ARG;
-    const int64_t n_pages = linear_pages(*s), tile_bytes = (int64_t)kTileN * kTileK * 2, tpp = s->page_bytes / tile_bytes;
-    std::vector<char> seen((size_t)pool_pages, 0);
-    for (int64_t p = 0; p < n_pages; ++p) {
-        const int32_t v = page_table[p];
-        if (v < 0 || v >= pool_pages) return MOE_ERR_PAGE_NOT_RESIDENT;
-        if (seen[(size_t)v]) return MOE_ERR_INVALID_ARG;
-        seen[(size_t)v] = 1;
-    }
-    const int64_t kt_n = s->K / kTileK, nt_n = s->N / kTileN, tiles = kt_n * nt_n;
-    auto tile_ptr = [&](int64_t ti) {
-        return (char*)pages_out + (int64_t)page_table[ti / tpp] * s->page_bytes + (ti % tpp) * tile_bytes;
-    };
-    for (int64_t ti = tiles; ti < n_pages * tpp; ++ti) std::memset(tile_ptr(ti), 0, (size_t)tile_bytes);   // padding of the last page
-    for (int64_t nt = 0; nt < nt_n; ++nt)
-        for (int64_t kt = 0; kt < kt_n; ++kt)
-            copy_tile(tile_ptr(nt * kt_n + kt), (char*)W + ((nt * kTileN) * (int64_t)s->K + kt * kTileK) * 2, s->K, 2, true);
-    return MOE_OK;
-}
 
 int moe_linear(const moe_linear_shape* s, const void* x, const int32_t* page_table, const void* page_pool,
                int64_t pool_pages, float* out, void* workspace, size_t workspace_bytes, int32_t* status, void* stream) {

@@ -184,6 +184,19 @@ def test_mixtral_8x7b_t256_with_the_row_copy():
         M.set_option("fuse_gather", 1)
 
 
+@pytest.mark.parametrize("T", [512, 1024, 1536, 2048])
+def test_mixtral_8x7b_around_the_ridge(T):
+    # micro-batch sizes on both sides of the point where a kernel execution turns compute bound (about 1000 tokens
+    # for this shape): the down launch takes its narrow column tiles up to 1024 tokens and the wide ones beyond, the
+    # experts have one to three row tiles, some of them tall, and the tile order switches its chunks on
+    cfg = scaled(CONFIGS["c3_mixtral8x7b_t4096"], name=f"ridge_t{T}", T=T)
+    case = Case(cfg)
+    ws, y = nan_filled_outputs(case)
+    M.moe_layer(case.shape, case.x, case.Wr, case.pw.table_dev, case.pw.pages_dev, workspace=ws, y=y)
+    torch.cuda.synchronize()
+    check_full(case, y, ws, cfg.name)
+
+
 def test_mixtral_8x7b_prefill_micro_batch():
     # a prefill micro-batch as the request batching forms it from a seeded prompt-length mix (average 77, maximum
     # 418, 128 requests per micro-batch): a token count that none of the tile sizes divides

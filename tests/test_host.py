@@ -192,3 +192,31 @@ def test_pipeline_pool_size_and_argument_errors_without_gpu():
         == B.ERR_INVALID_ARG
     assert lib.moe_pipeline_run(None, 1, None, None, None, None, None, None, 0, None, None) == B.ERR_INVALID_ARG
     assert lib.moe_pipeline_destroy(None) == B.ERR_INVALID_ARG
+
+
+def test_host_packer_and_oracle_under_the_host_sanitizers(tmp_path):
+    """The host-only translation unit of the library (csrc/moe_host.cpp: shape checks, page geometry, packer) and the C
+    oracle, built with the host compiler's address and undefined-behaviour sanitizers and run on exact-size heap
+    buffers (tests/sanitize_driver.cpp): an access outside a buffer, a signed overflow or a misaligned access in
+    either ends the program with a report."""
+    import shutil
+    import subprocess
+    if not (shutil.which("gcc") and shutil.which("g++")):
+        pytest.skip("no host compiler")
+    san = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-g", "-O1",
+           "-I", os.path.join(ROOT, "include"), "-I", os.path.join(ROOT, "paper_2411_11217_amd", "csrc")]
+    objs = []
+    for cc, std, src in (("gcc", "-std=c11", os.path.join(ROOT, "oracle", "moe_oracle.c")),
+                         ("g++", "-std=c++17", os.path.join(ROOT, "paper_2411_11217_amd", "csrc", "moe_host.cpp")),
+                         ("g++", "-std=c++17", os.path.join(ROOT, "tests", "sanitize_driver.cpp"))):
+        obj = str(tmp_path / (os.path.basename(src) + ".o"))
+        r = subprocess.run([cc, std, "-fopenmp", "-pthread"] + san + ["-c", src, "-o", obj], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr[-4000:]
+        objs.append(obj)
+    exe = str(tmp_path / "sanitize_driver")
+    r = subprocess.run(["g++", "-fopenmp", "-pthread"] + san + objs + ["-o", exe, "-lm"], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-4000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1", OMP_NUM_THREADS="4")
+    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
+    assert r.returncode == 0, (r.stdout[-2000:], r.stderr[-4000:])
+    assert "all ok" in r.stdout and "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr
