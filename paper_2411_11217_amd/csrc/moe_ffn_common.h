@@ -4,6 +4,7 @@
 #pragma once
 
 #include "moe_internal.h"
+#include "moe_tile_order.h"
 
 namespace moe {
 
@@ -45,21 +46,13 @@ struct TileCoord {
     bool valid;
 };
 
-// Tile order.  The row tiles of one column tile of one expert form a GROUP (they share
-// the weight tiles); the groups of an expert are taken in CHUNKS of G consecutive column
-// tiles, G = max(1, 32 / row tiles of the expert): about as many tiles as an XCD has compute
-// units.  With xcd_remap the chunks, numbered expert by expert, are dealt round robin to the
-// 8 XCDs (block b runs on XCD b % 8, each with its own L2): the blocks an XCD runs at the
-// same time are then the row tiles of G column tiles of ONE expert, so an activation row tile
-// is fetched into that L2 once for G blocks and a weight tile once for all its row tiles
-// (dealing single groups round robin left only NT / 8 groups of an expert on an XCD: two in
-// the down projection of the Mixtral-8x7B shape, where every activation row tile then crossed
-// the fabric once per pair of blocks).  Without xcd_remap all chunks belong to one sequence.
-// The tile counts come from offsets[], so the grid is only an upper bound and surplus blocks
-// leave at once.
+// Block -> tile.  The order of the tiles is that of moe_tile_order.h (chunks of about 32 tiles of one expert, dealt
+// round robin to the 8 XCDs: block b runs on XCD b % 8, each with its own L2; without xcd_remap all chunks belong
+// to one sequence).  The tile counts come from offsets[], so the host never needs the routing result; the grid is
+// only an upper bound and surplus blocks leave at once.
 //
 // Every wavefront does the search on its own, one expert per lane (at most 64
-// experts): one load of the segment bounds, prefix sums of the tile counts over
+// experts): one load of the segment bounds, prefix sums of the chunk and tile counts over
 // the lanes, a ballot to find the expert that holds the tile number.  The result
 // is the same in all lanes.
 __device__ __forceinline__ int lane_prefix_sum(int v, int lane) {
@@ -71,13 +64,7 @@ __device__ __forceinline__ int lane_prefix_sum(int v, int lane) {
     return v;
 }
 
-// Tall tiles that take a remainder of r rows along with q full tiles (0 < r <= tall_rows * q).  A tall tile with at
-// most 16 extra rows costs half as many extra MFMAs as one with 17 .. 32 (bf16 kernel), so the remainder goes to
-// ceil(r / 16) tiles when there are that many, else to as few tiles as possible (ceil(r / tall_rows)).
-__device__ __forceinline__ int tall_tiles_of(int r, int q, int tall_rows) {
-    const int m16 = (r + 15) / 16;
-    return m16 <= q ? m16 : (r + tall_rows - 1) / tall_rows;
-}
+__device__ __forceinline__ int uniform_of(int v_l, int src) { return __builtin_amdgcn_readfirstlane(__shfl(v_l, src, 64)); }
 
 template <int BM>
 __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
@@ -93,84 +80,42 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
     const int stride = p.xcd_remap ? 8 : 1;
     const int x = p.xcd_remap ? (int)(blockIdx.x & 7) : 0;           // my chunks: those whose number is x modulo stride
     const int idx = p.xcd_remap ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;    // my position among their tiles
-    // row tiles of my lane's expert.  q full tiles and a remainder r: when r <= tall_rows * q the remainder is
-    // spread over the last tall_tiles_of(r, q) of the q tiles (each at most BM + tall_rows rows high), otherwise it is
-    // a tile of its own
-    const int q_l = cnt / BM, r_l = cnt - q_l * BM;
-    const bool rides_l = q_l >= 1 && r_l > 0 && r_l <= p.tall_rows * q_l;
-    const int mtiles_l = rides_l ? q_l : q_l + (r_l > 0);
-    const int tall_l = rides_l ? tall_tiles_of(r_l, q_l, p.tall_rows) : 0;
-    // chunks of my lane's expert: nch_l = ceil(NT / G) of them, of Gc_l or Gc_l + 1 groups each (the first big_l ones are
-    // the bigger: equal sizes keep the XCDs' shares equal when the groups do not divide); an expert without rows has none
-    const int G_l = (p.chunked && cnt > BM / 2) ? min(max(1, p.chunked / max(mtiles_l, 1)), 8) : 1;      // p.chunked: tiles a chunk aims at (32); at most 8 groups
-    const int nch_l = mtiles_l > 0 ? (p.NT + G_l - 1) / G_l : 0;
-    const int Gc_l = p.NT / max(nch_l, 1), big_l = p.NT - Gc_l * nch_l;
-    const int cb_l = lane_prefix_sum(nch_l, lane) - nch_l;          // chunks of the experts before mine
-    int c0_l = (x - cb_l) % stride;                                  // my first chunk in this expert
-    if (c0_l < 0) c0_l += stride;
-    const int mine_l = c0_l < nch_l ? (nch_l - 1 - c0_l) / stride + 1 : 0;
-    const int bigmine_l = c0_l < big_l ? (big_l - 1 - c0_l) / stride + 1 : 0;      // my chunks among the bigger ones: my first ones
-    const int groups_l = mine_l * Gc_l + bigmine_l;
-    const int tiles_l = groups_l * mtiles_l;
+    // my lane's expert: its row tiles, its chunks, and what my XCD gets of each of its row blocks
+    const RowTiles rt_l = row_tiles_of(cnt, BM, p.tall_rows);
+    const ChunkPlan c_l = plan_chunks(rt_l.mtiles, cnt <= BM / 2, p.NT, p.chunked);
+    const int chunks_l = c_l.nb * c_l.nch;
+    const int cb_l = lane_prefix_sum(chunks_l, lane) - chunks_l;    // chunks of the experts before mine
+    int tiles_l = 0;
+    for (int b = 0; b < c_l.nb; ++b) tiles_l += share_of_block(c_l, b, x - cb_l, stride).tiles;
     const int incl = lane_prefix_sum(tiles_l, lane);
     if (idx >= __builtin_amdgcn_readlane(incl, 63)) return t;
     const unsigned long long holds = __ballot(idx < incl);           // lanes of this and later experts
     const int src = __builtin_amdgcn_readfirstlane(__ffsll((long long)holds) - 1);
-    const int mtiles = __builtin_amdgcn_readfirstlane(__shfl(mtiles_l, src, 64));
-    const int tall = __builtin_amdgcn_readfirstlane(__shfl(tall_l, src, 64));
-    const int Gc = __builtin_amdgcn_readfirstlane(__shfl(Gc_l, src, 64));
-    const int big = __builtin_amdgcn_readfirstlane(__shfl(big_l, src, 64));
-    const int bigmine = __builtin_amdgcn_readfirstlane(__shfl(bigmine_l, src, 64));
-    const int c0 = __builtin_amdgcn_readfirstlane(__shfl(c0_l, src, 64));
-    const int before = __builtin_amdgcn_readfirstlane(__shfl(incl - tiles_l, src, 64));
-    const int seg = __builtin_amdgcn_readfirstlane(__shfl(seg0, src, 64));
-    const int rows = __builtin_amdgcn_readfirstlane(__shfl(cnt, src, 64));
-    const int rem = idx - before;
-    // my chunks in their order: bigmine of Gc + 1 groups, then the others of Gc groups
-    const int in_big = bigmine * (Gc + 1) * mtiles;
-    const int ci = rem < in_big ? rem / ((Gc + 1) * mtiles) : bigmine + (rem - in_big) / (Gc * mtiles);
-    const int c = c0 + ci * stride;                                  // chunk number inside the expert
-    const int g_c = Gc + (c < big);                                  // its groups
-    const int r2 = rem - (ci <= bigmine ? ci * (Gc + 1) : in_big / mtiles + (ci - bigmine) * Gc) * mtiles;      // my tile inside the chunk
-    const int G0 = c * Gc + min(c, big);                             // its first group
-    // Order inside a chunk.  Blocks are handed to compute units first come, first served, and a tall tile
-    // takes longer than the others.  The tall tiles of all groups of the chunk come first, then the other
-    // tiles group by group: the compute units that arrive first get the long tiles, those that arrive late
-    // (they had a long tile the last time) get ordinary ones, and the blocks that run at the same time keep
-    // reading the same stretch of the operands they share.  Numbered with the tall tile last in its group,
-    // the late compute units would meet the next tall tile again and fall further behind with every round.
-    int jj, mt;
-    if (p.tall_first && tall > 0 && r2 < g_c * tall) {
-        jj = r2 / tall;
-        mt = (mtiles - tall) + (r2 - jj * tall);
-    } else if (p.tall_first && tall > 0) {
-        const int r3 = r2 - g_c * tall, plain = mtiles - tall;       // plain >= 1: tiles remain behind the tall ones
-        jj = r3 / plain;
-        mt = r3 - jj * plain;
-    } else {
-        jj = r2 / mtiles;
-        mt = r2 - jj * mtiles;
+    const int mtiles = uniform_of(rt_l.mtiles, src), tall = uniform_of(rt_l.tall, src);
+    ChunkPlan c;
+    c.nb = uniform_of(c_l.nb, src);
+    c.rb = uniform_of(c_l.rb, src);
+    c.rbig = uniform_of(c_l.rbig, src);
+    c.nch = uniform_of(c_l.nch, src);
+    c.Gc = uniform_of(c_l.Gc, src);
+    c.big = uniform_of(c_l.big, src);
+    const int xrel = x - uniform_of(cb_l, src);
+    const int seg = uniform_of(seg0, src), rows = uniform_of(cnt, src);
+    int rem = idx - uniform_of(incl - tiles_l, src);                 // my tile among my XCD's tiles of this expert
+    int b = 0;
+    BlockShare s = share_of_block(c, 0, xrel, stride);
+    while (b + 1 < c.nb && rem >= s.tiles) {                         // the row block that holds it
+        rem -= s.tiles;
+        ++b;
+        s = share_of_block(c, b, xrel, stride);
     }
-    t.nt = G0 + jj;
-    t.mt = mt;
+    const TileInExpert te = tile_in_block(c, b, s, rem, stride, mtiles, tall, p.tall_first != 0);
+    const RowSpan rs = rows_of_tile(seg, rows, te.mt, BM, p.tall_rows);
+    t.nt = te.nt;
+    t.mt = te.mt;
     t.e = p.e_begin + src;
-    const int q = rows / BM, r = rows - q * BM;
-    if (r > 0 && q >= 1 && r <= p.tall_rows * q) {
-        // the last m tiles are BM + r / m rows high, the first r % m of them one row more
-        const int m = tall_tiles_of(r, q, p.tall_rows), plain = q - m;
-        const int i = t.mt - plain;
-        if (i < 0) {
-            t.row0 = seg + t.mt * BM;
-            t.rows_here = BM;
-        } else {
-            const int base = BM + r / m, more = r - (r / m) * m;
-            t.row0 = seg + plain * BM + i * base + min(i, more);
-            t.rows_here = base + (i < more);
-        }
-    } else {
-        t.row0 = seg + t.mt * BM;
-        t.rows_here = min(BM, rows - t.mt * BM);
-    }
+    t.row0 = rs.row0;
+    t.rows_here = rs.rows_here;
     t.valid = t.rows_here > 0;
     return t;
 }
@@ -186,27 +131,6 @@ __device__ __forceinline__ const char* tile_address(const GemmParams& p, const i
         slot = 0;
     }
     return p.pool + (int64_t)slot * p.page_bytes + (int64_t)within * p.tile_bytes;
-}
-
-// Grid size that covers every tile for any routing result.  M = R / BM + n_experts bounds the sum of the experts'
-// row tiles.  Dealing single groups round robin, an XCD gets at most ceil(NT / 8) groups of an expert: ceil(NT / 8) * M
-// tiles.  Dealt in chunks, an expert with m row tiles (G = min(8, max(1, chunk_tiles / m)) groups per chunk, nch =
-// ceil(NT / G) chunks of Gc = NT / nch groups, NT - Gc * nch of them one group more) gives an XCD at most
-// ceil(nch / 8) chunks, of which at most ceil(big / 8) are the bigger ones; the most that exceeds ceil(NT / 8) * m
-// for any m is added once per expert.  (Blocks beyond the tiles leave at once, but each still costs about a
-// microsecond of a compute unit: the bound is kept tight.)
-inline int gemm_grid(int NT, int R, int BM, int n_experts, int chunk_tiles = 32) {
-    const int64_t M = R / BM + n_experts;
-    const int64_t plain_groups = (NT + 7) / 8;
-    int64_t slack = 0;
-    for (int m = 1; m <= chunk_tiles; ++m) {
-        const int G = std::min(std::max(1, chunk_tiles / m), 8);
-        if (G == 1) continue;                                         // single groups: no more than ceil(NT / 8) * m
-        const int nch = (NT + G - 1) / G, Gc = NT / nch, big = NT - Gc * nch;
-        const int64_t mine = (nch + 7) / 8, bigmine = std::min<int64_t>((big + 7) / 8, mine);
-        slack = std::max(slack, (mine * Gc + bigmine) * m - plain_groups * m);
-    }
-    return (int)(8 * (plain_groups * M + slack * n_experts));
 }
 
 inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const FfnArgs& a) {

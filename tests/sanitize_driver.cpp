@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "moe.h"
+#include "moe_tile_order.h"
 
 extern "C" {
 void oracle_route(int T, int H, int E, int k, int dtype, const void* x, const void* Wr, const double* bias, int32_t* ids,
@@ -155,7 +156,108 @@ static void oracle_layer(int dtype, int T, int H, int F, int E, int k, bool with
     std::printf("oracle dtype=%d T=%d H=%d F=%d E=%d k=%d bias=%d: ok\n", dtype, T, H, F, E, k, (int)with_bias);
 }
 
+// The tile order of the expert GEMMs, evaluated the way the kernels do (per expert: row tiles, chunk plan, the share of
+// every XCD; per block: the expert by cumulative tile counts, the row block, the tile): every tile of every expert is
+// taken by exactly one block, the row tiles partition the segments, and no XCD has more tiles than the grid gives it.
+static void tile_order(const std::vector<int>& counts, int NT, int BM, int tall_rows, int chunked, int stride, bool tall_first) {
+    using namespace moe;
+    const int E = (int)counts.size();
+    int R = 0;
+    for (int c : counts) R += c;
+    const int grid = gemm_grid(NT, R, BM, E, chunked);
+    CHECK(grid % 8 == 0);
+    std::vector<RowTiles> rt((size_t)E);
+    std::vector<ChunkPlan> plan((size_t)E);
+    std::vector<int> cb((size_t)E), seg((size_t)E);
+    int chunks = 0, rows0 = 0;
+    size_t total = 0;
+    for (int e = 0; e < E; ++e) {
+        rt[(size_t)e] = row_tiles_of(counts[(size_t)e], BM, tall_rows);
+        plan[(size_t)e] = plan_chunks(rt[(size_t)e].mtiles, counts[(size_t)e] <= BM / 2, NT, chunked);
+        cb[(size_t)e] = chunks;
+        seg[(size_t)e] = rows0;
+        chunks += plan[(size_t)e].nb * plan[(size_t)e].nch;
+        rows0 += counts[(size_t)e];
+        total += (size_t)rt[(size_t)e].mtiles * NT;
+        // the row tiles partition the segment, none higher than BM + tall_rows, tall ones last
+        int next = seg[(size_t)e];
+        for (int mt = 0; mt < rt[(size_t)e].mtiles; ++mt) {
+            const RowSpan rs = rows_of_tile(seg[(size_t)e], counts[(size_t)e], mt, BM, tall_rows);
+            CHECK(rs.row0 == next && rs.rows_here > 0 && rs.rows_here <= BM + tall_rows);
+            CHECK((rs.rows_here > BM) == (mt >= rt[(size_t)e].mtiles - rt[(size_t)e].tall));
+            next += rs.rows_here;
+        }
+        CHECK(next == seg[(size_t)e] + counts[(size_t)e]);
+    }
+    std::vector<std::vector<char>> seen((size_t)E);
+    for (int e = 0; e < E; ++e) seen[(size_t)e].assign((size_t)rt[(size_t)e].mtiles * NT, 0);
+    size_t taken = 0;
+    for (int x = 0; x < stride; ++x) {
+        std::vector<int> tiles((size_t)E, 0);
+        int mine = 0;
+        for (int e = 0; e < E; ++e) {
+            for (int b = 0; b < plan[(size_t)e].nb; ++b) tiles[(size_t)e] += share_of_block(plan[(size_t)e], b, x - cb[(size_t)e], stride).tiles;
+            mine += tiles[(size_t)e];
+        }
+        CHECK(mine <= (stride == 8 ? grid / 8 : grid));                   // the grid reaches every tile of this XCD
+        int last_e = -1, last_chunk_nt = -1;
+        (void)last_e; (void)last_chunk_nt;
+        for (int idx = 0; idx < mine; ++idx) {
+            int e = 0, before = 0;
+            while (idx >= before + tiles[(size_t)e]) before += tiles[(size_t)e++];
+            const ChunkPlan& c = plan[(size_t)e];
+            int rem = idx - before, b = 0;
+            BlockShare s = share_of_block(c, 0, x - cb[(size_t)e], stride);
+            while (b + 1 < c.nb && rem >= s.tiles) {
+                rem -= s.tiles;
+                ++b;
+                s = share_of_block(c, b, x - cb[(size_t)e], stride);
+            }
+            CHECK(rem < s.tiles);
+            const TileInExpert te = tile_in_block(c, b, s, rem, stride, rt[(size_t)e].mtiles, rt[(size_t)e].tall, tall_first);
+            CHECK(te.mt >= 0 && te.mt < rt[(size_t)e].mtiles && te.nt >= 0 && te.nt < NT);
+            char& flag = seen[(size_t)e][(size_t)te.mt * NT + te.nt];
+            CHECK(flag == 0);
+            flag = 1;
+            ++taken;
+        }
+    }
+    CHECK(taken == total);
+}
+
+static void tile_orders() {
+    std::uniform_int_distribution<int> small(0, 700), large(0, 20000), pick(0, 9);
+    int cases = 0;
+    for (int NT : {1, 2, 7, 16, 24, 56, 112}) {
+        for (int chunked : {0, 32}) {
+            for (int stride : {8, 1}) {
+                for (int tall_rows : {0, 32}) {
+                    for (int rep = 0; rep < 6; ++rep) {
+                        const int E = 1 + (int)(g_rng() % 17);
+                        std::vector<int> counts((size_t)E);
+                        for (int& c : counts) {
+                            const int kind = pick(g_rng);
+                            c = kind == 0 ? 0 : kind < 6 ? small(g_rng) : kind < 9 ? 256 * (1 + (int)(g_rng() % 40)) + (int)(g_rng() % 64) : large(g_rng);
+                        }
+                        tile_order(counts, NT, 256, tall_rows, chunked, stride, rep % 2 == 0);
+                        ++cases;
+                    }
+                }
+            }
+        }
+    }
+    // one expert beyond the row-block limit, the headline routing, a skewed one, exact multiples
+    tile_order({256 * 300 + 5, 10, 0, 4000}, 56, 256, 32, 32, 8, true);
+    tile_order({1027, 1061, 1029, 995, 1046, 1010, 1014, 1010}, 112, 256, 32, 32, 8, true);
+    tile_order({6500, 3000, 2500, 1800, 1200, 800, 400, 184}, 128, 256, 32, 32, 8, true);
+    tile_order({1024, 1024, 1024, 1024}, 16, 256, 32, 32, 8, true);
+    tile_order({4096}, 24, 256, 32, 32, 8, true);
+    tile_order({300, 200, 100}, 4, 64, 0, 32, 8, false);                 // the f32 kernel's row tile
+    std::printf("tile order: %d random cases and 6 fixed ones ok\n", cases);
+}
+
 int main() {
+    tile_orders();
     // packer: tiles that fill their pages exactly, pages with padding at the end of a group, one tile per page
     packer_round_trip(MOE_DTYPE_F32, 128, 256, 3, 2 * 32768);
     packer_round_trip(MOE_DTYPE_F32, 256, 128, 2, 5 * 32768);
