@@ -71,13 +71,6 @@ namespace {
 
 #define MOE_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-#ifdef MOE_TIMELINE      // experimental builds only: per block, wall-clock stamps (100 MHz) at the start, every 16 k-steps and at the end
-__device__ long long g_timeline[2 * 8192 * 24];
-#define MOE_TL_STAMP() do { if (tid == 0 && tli < 23) tl[tli++] = wall_clock64(); } while (0)
-#else
-#define MOE_TL_STAMP() do { } while (0)
-#endif
-
 typedef int i32x4 __attribute__((ext_vector_type(4)));        // an MFMA operand: 8 bf16 in four registers
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) const void* gptr_t;
@@ -139,25 +132,15 @@ __device__ __forceinline__ void mfma_16x16x32(const i32x4& a, const i32x4& b) { 
 // wait state the load needs after it), global address base + offset[lane].  One statement, so nothing
 // can come between the write of M0 and the load; the scalar base + 32-bit lane offset form of the load
 // needs no 64-bit vector addition (the builtin's flat-pointer form costs one per load).
-// CPOL: cache-policy bits of the load (0 = default, 1 = nt, 2 = sc0, 3 = sc1, 4 = sc0 sc1; build-time experiments).
-#ifndef MOE_CPOL_A
-#define MOE_CPOL_A 0
-#endif
-#ifndef MOE_CPOL_B
-#define MOE_CPOL_B 0
-#endif
-#define MOE_MFMA_THEN_LOAD(MODIFIERS)                                                                                          \
-    asm volatile("s_add_i32 m0, %4, %5\n\tv_mfma_f32_16x16x32_bf16 a[%6:%7], %0, %1, a[%6:%7]\n\tglobal_load_lds_dwordx4 %2, %3" MODIFIERS \
-                 ::"v"(a), "v"(b), "v"(offset), "s"(base), "s"(lds_base), "n"(LDS_IMM), "n"(R), "n"(R + 3)                      \
-                 : "memory", "m0")
-template <int R, int LDS_IMM, int CPOL = 0>
+// (The compiler puts an s_nop in front of every such statement that follows another within a few instructions, because
+// M0 is on the clobber list: six per half-step.  They issue in the shadow of an MFMA: a build without the clobber,
+// and so without them, was not faster.)
+template <int R, int LDS_IMM>
 __device__ __forceinline__ void mfma_16x16x32_then_load(const i32x4& a, const i32x4& b, const char* base, uint32_t offset, uint32_t lds_base) {
 #ifdef __HIP_DEVICE_COMPILE__
-    if constexpr (CPOL == 0) MOE_MFMA_THEN_LOAD("");
-    else if constexpr (CPOL == 1) MOE_MFMA_THEN_LOAD(" nt");
-    else if constexpr (CPOL == 2) MOE_MFMA_THEN_LOAD(" sc0");
-    else if constexpr (CPOL == 3) MOE_MFMA_THEN_LOAD(" sc1");
-    else MOE_MFMA_THEN_LOAD(" sc0 sc1");
+    asm volatile("s_add_i32 m0, %4, %5\n\tv_mfma_f32_16x16x32_bf16 a[%6:%7], %0, %1, a[%6:%7]\n\tglobal_load_lds_dwordx4 %2, %3"
+                 ::"v"(a), "v"(b), "v"(offset), "s"(base), "s"(lds_base), "n"(LDS_IMM), "n"(R), "n"(R + 3)
+                 : "memory", "m0");
 #endif
 }
 // The same MFMA with its accumulator tile in vector registers the compiler allocates, and a plain 16-byte load
@@ -292,19 +275,6 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         probe_w = wall_clock64();
     }
     const int e = tc.e, nt = tc.nt, row0 = tc.row0, rows_here = tc.rows_here;
-#ifdef MOE_TIMELINE
-    long long* tl = g_timeline + ((size_t)MODE * 8192 + (blockIdx.x & 8191)) * 24;
-    int tli = 1;
-    if (tid == 0) tl[0] = ((long long)rows_here << 48) | ((long long)e << 40) | ((long long)tc.mt << 24) | (long long)nt;
-    MOE_TL_STAMP();
-#endif
-    if (p.stagger_ticks > 0 && (blockIdx.x >> 3) < 32) {       // the first block of a compute unit
-        const int unit = p.stagger_mode == 0 ? (tc.mt & 3) : p.stagger_mode == 1 ? (int)((blockIdx.x >> 3) & 31)
-                       : p.stagger_mode == 2 ? (int)(((blockIdx.x >> 3) >> 2) & 7) : (int)(blockIdx.x & 7);
-        const long long until = wall_clock64() + (long long)unit * p.stagger_ticks;
-        for (int spin = 0; spin < 100000 && wall_clock64() < until; ++spin) __builtin_amdgcn_s_sleep(4);
-    }
-
     // With a_gather the activation rows come from the matrix at A through an index: lane L of the wavefront
     // looks up the source of the wavefront's row (L / 8 * 4 + wave) * 8 + L % 8 here (one division per lane,
     // the load under way during the page-table lookups).
@@ -481,13 +451,13 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     };
     auto mfma_load_a = [&](auto i_c, auto j_c, const i32x4& a, const i32x4& b, auto ia_c) __attribute__((always_inline)) {   // + activation load instruction IA
         constexpr int IA = decltype(ia_c)::value;
-        mfma_16x16x32_then_load<(decltype(i_c)::value * NJ + decltype(j_c)::value) * 4, IA * kWaves * 1024, MOE_CPOL_A>(a, b, a_ptr, a_off[IA], a_wr_w);
+        mfma_16x16x32_then_load<(decltype(i_c)::value * NJ + decltype(j_c)::value) * 4, IA * kWaves * 1024>(a, b, a_ptr, a_off[IA], a_wr_w);
         advance_a(IA);
     };
     auto mfma_load_b = [&](auto i_c, auto j_c, const i32x4& a, const i32x4& b, auto slot_c, auto l_c, int kn) __attribute__((always_inline)) {   // + weight load instruction L of half-step kn into slot SLOT
         constexpr int SLOT = decltype(slot_c)::value, I = decltype(l_c)::value;
         constexpr int odd = SLOT & 1;               // S is even: the parity of the half-step is that of its slot
-        mfma_16x16x32_then_load<(decltype(i_c)::value * NJ + decltype(j_c)::value) * 4, SLOT * kStageB + (I >= 2 ? kHalfTile : 0) + (I & 1) * (kWaves * 1024), MOE_CPOL_B>(
+        mfma_16x16x32_then_load<(decltype(i_c)::value * NJ + decltype(j_c)::value) * 4, SLOT * kStageB + (I >= 2 ? kHalfTile : 0) + (I & 1) * (kWaves * 1024)>(
             a, b, (I < 2 ? w0 : w1).tile, b_voff[odd][I & 1], lds_wave);
         advance_b(kn, odd, I);
     };
@@ -566,6 +536,13 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                         MOE_FENCE();
                     }
                 });
+                // Every fragment fetched above is in its registers by now (the last fetch is NMF - NF1 MFMAs old).  Said
+                // with ONE full wait: left to itself the compiler either does the same or, when it can count the
+                // outstanding fetches exactly (seen when a wait instruction stood in front of the loop), puts a counted
+                // wait in front of every MFMA that uses a fragment for the first time - ten more instructions per
+                // half-step for the one wavefront of the SIMD to issue.
+                __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
+                MOE_FENCE();
                 constexpr int LB0 = NB == 2 ? 8 : 6, LBS = NB == 2 ? 6 : 5;             // MFMAs with a weight load behind them
                 static_for<NMF>([&](auto mc) __attribute__((always_inline)) {
                     constexpr int m = decltype(mc)::value;
@@ -583,12 +560,10 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                     if constexpr (NJ == 8) mfma_extra_tile_8<MODE == 0>(accE, AE[U], BF[HP], extra_which);
                     else mfma_extra_tile_4(accE, AE[U], BF[HP], extra_which);
                     MOE_FENCE();
-#ifndef MOE_TALL_NOLOAD      // (timing experiment only: the extra tile without its loads)
                     // the fragment of half-step k + 4: there is one exactly while the activation loads go on (the last four
                     // half-steps run without LA), so no test of k is needed
                     if constexpr (LA) load_vgpr_16(AE[U], ae_ptr + (int64_t)(k + 4) * 64);
                     MOE_FENCE();
-#endif
                 }
             } else if (wact) {
                 constexpr int NH = NJ / 2, NG = RT * NH;            // column fragments and MFMAs of a group
@@ -611,6 +586,8 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                         }
                     });
                 });
+                __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0): as in the full loop
+                MOE_FENCE();
                 constexpr int LBS = NG / (2 * NB);                  // every LBS-th MFMA has a weight load behind it
                 static_for<NG>([&](auto mc) __attribute__((always_inline)) {
                     constexpr int m = decltype(mc)::value;
@@ -671,9 +648,6 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         static_for<32 * NJ>([&](auto rc) __attribute__((always_inline)) { acc_zero<decltype(rc)::value>(); });
         int k = 0;
         for (; k + S < KH; k += S) {
-#ifdef MOE_TIMELINE
-            if ((k & 31) == 0) MOE_TL_STAMP();
-#endif
             half_step(k, integral_constant<int, 0>{}, L, L, integral_constant<int, kL2>{});
             half_step(k + 1, integral_constant<int, 1>{}, L, L, integral_constant<int, kL2>{});
             half_step(k + 2, integral_constant<int, 2>{}, L, L, integral_constant<int, kL2>{});
@@ -813,10 +787,6 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
             }
         }
     }
-#ifdef MOE_TIMELINE
-    MOE_TL_STAMP();
-    if (tid == 0) tl[23] = tli;
-#endif
     if (clock_probe) {
         const long long dc = clock64() - probe_c, dw = wall_clock64() - probe_w;
         if (dw > 0) p.status[2 + MODE] = (int32_t)(dc * 100 / dw);       // MHz
@@ -839,18 +809,6 @@ int launch_stages(const GemmParams& p, int grid, hipStream_t st) {
 }
 
 }  // namespace
-
-#ifdef MOE_TIMELINE
-extern "C" int moe_debug_timeline_read(void* dst, size_t bytes) {
-    return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_timeline), bytes < sizeof(g_timeline) ? bytes : sizeof(g_timeline));
-}
-extern "C" int moe_debug_timeline_clear() {
-    void* ptr = nullptr;
-    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_timeline));
-    if (e != hipSuccess) return (int)e;
-    return (int)hipMemset(ptr, 0, sizeof(g_timeline));
-}
-#endif
 
 int launch_expert_ffn_bf16(const moe_shape& s, const Geom& g, const FfnArgs& a, hipStream_t st) {
     const int R = s.T * s.k;

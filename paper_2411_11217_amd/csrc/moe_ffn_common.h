@@ -37,8 +37,6 @@ struct GemmParams {
     int32_t tall_rows;        // bf16 kernel: a row tile may be up to this many rows higher than BM (0 or 32), see locate_tile
     int32_t chunked;          // tile numbering: groups dealt to the XCDs in chunks of about this many tiles (0: single groups), see locate_tile
     int32_t tall_first;       // bf16 kernel: tile numbering with the tall tiles of a chunk of groups first, see locate_tile
-    int32_t stagger_ticks;    // bf16 kernel: start delay unit of a compute unit's first block, in ticks of the 100 MHz counter
-    int32_t stagger_mode;
 };
 
 struct TileCoord {
@@ -154,8 +152,6 @@ inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const 
     // the weights, single groups spread over the XCDs are the better order, and the grid needs no slack for chunks
     const int64_t rows_each = (int64_t)s.T * s.k / std::max(1, a.e_end - a.e_begin);
     p.chunked = rows_each > 128 ? std::min(std::max(get_opt(OPT_CHUNKED), 0), 32) : 0;
-    p.stagger_ticks = get_opt(OPT_STAGGER_NS) / 10;
-    p.stagger_mode = get_opt(OPT_STAGGER_MODE);
 }
 
 // parameters of the gate/up launch (K = H, output h[R][F]) and of the down launch
