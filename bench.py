@@ -26,7 +26,7 @@ PEAK_CLOCK_MHZ = 2400.0       # the clock the published peaks are quoted at
 
 # HBM traffic per launch of the gate/up GEMM on the default workload, in bytes, from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/ (None: not measured).
-MEASURED_TRAFFIC = {"c3_mixtral8x7b_t4096": 5.454e9}
+MEASURED_TRAFFIC = {"c3_mixtral8x7b_t4096": 3.394e9, "c2_mixtral8x7b_t256": 1.935e9, "c4_mixtral8x22b_t8192_skew": 2.172e10}
 
 
 def cpu_model() -> str:
@@ -73,6 +73,7 @@ def main():
                     help="instead of the headline step, time moe_layer on --config's layer shape (weights resident) for "
                          "micro-batch sizes 32 .. 4096: the memory-bound plateau of the decode stage (the paper's section "
                          "6.2 sweeps 32 .. 256) and the turn to compute bound beyond it")
+    ap.add_argument("--mu-list", default="", help="--mu-sweep: comma-separated micro-batch sizes instead of the default 32 .. 4096")
     ap.add_argument("--rate-probes", action="store_true",
                     help="instead of the layer, measure the three rates the roofline model takes as its inputs, each with a "
                          "probe that is none of the layer runs the model is then asked to predict: the host link with a "
@@ -188,12 +189,21 @@ def main():
                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get(args.config),
                     "avg_launch_ms": round(stages["gemm_gate_up"], 4), "launches_timed": n_prof}
+        # Few rows per expert (at most half a row tile on average): the launch streams the weights once and HBM is its
+        # roof.  Algorithmic bytes: both weight matrices of every expert, x, and h written.
+        esize = 2 if cfg.dtype == "bf16" else 4
+        if cfg.R <= 128 * cfg.E:
+            gu_bytes = 2.0 * cfg.E * cfg.H * cfg.F * esize + cfg.T * cfg.H * esize + cfg.R * cfg.F * esize
+            gbs = gu_bytes / t_gu / 1e9
+            roofline.update({"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                             "frac": round(gbs / PEAK_HBM_GBS, 4), "mfma_tflops": round(achieved, 2)})
         # the shader clock a block of the launch saw (the chip is power limited under this kernel; the
         # published peak is for 2400 MHz), and the fraction of the peak at that clock
         st = ws.view("status").cpu().tolist()
         if cfg.dtype == "bf16" and st[2] > 0:
             roofline["clock_mhz"] = {"gate_up": st[2], "down": st[3]}
-            roofline["frac_at_that_clock"] = round(achieved / (PEAK_BF16_TFLOPS * st[2] / PEAK_CLOCK_MHZ), 4)
+            if roofline["bound"] == "mfma":
+                roofline["frac_at_that_clock"] = round(achieved / (PEAK_BF16_TFLOPS * st[2] / PEAK_CLOCK_MHZ), 4)
     extra = {}
     if stages:
         t_ffn = (stages["gemm_gate_up"] + stages["gemm_down"]) * 1e-3
@@ -373,7 +383,7 @@ def mu_sweep_bench(args, cfg, M, make_inputs):
     import torch
     from paper_2411_11217_amd import hrm
     inp = make_inputs(cfg, threads=16)
-    mus = [32, 64, 128, 256, 512, 1024, 2048, 4096]
+    mus = [int(v) for v in args.mu_list.split(",")] if args.mu_list else [32, 64, 128, 256, 512, 1024, 2048, 4096]
     s_max = M.make_shape(max(mus), cfg.H, cfg.F, cfg.E, cfg.k, cfg.dtype, cfg.page_bytes)
     pw = M.PagedWeights(s_max, inp["W1"], inp["W3"], inp["W2"])
     pw.to_device(keep_host=False)
