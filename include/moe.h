@@ -351,6 +351,8 @@ int moe_pre_attention(const moe_linear_shape* qkv_proj, const float* hidden, con
  *   "chunked"     tile order of the expert GEMMs: the column tiles of an expert go to the XCDs
  *                 in chunks of about this many tiles (at most 32); 0: one by one.  default 32
  *   "tall_first"  1: inside a chunk the tall row tiles are numbered first.       default 1
+ *   "balance"     1: no XCD runs more than an eighth of the tiles of an expert-GEMM launch: one
+ *                 that was dealt more gives its last tiles to XCDs with fewer.   default 1
  *   "profile"     1: moe_layer records stage events (see below).  Setting it to 1 creates
  *                 the events (the only option whose setter touches the device; it may
  *                 return MOE_ERR_HIP); the layer calls themselves create nothing.  default 0 */

@@ -866,6 +866,7 @@ int launch_linear_bf16(const LinearArgs& a, hipStream_t st) {
     p.half_tiles = get_opt(OPT_HALF_TILES);
     p.tall_rows = get_opt(OPT_TALL_TILES) ? 32 : 0;
     p.tall_first = get_opt(OPT_TALL_FIRST);
+    p.balance = get_opt(OPT_BALANCE);
     p.chunked = std::min(std::max(get_opt(OPT_CHUNKED), 0), 32);
     const int wide_tiles = (p.n_page_tiles + 1) / 2;
     if ((int64_t)(a.T / BM + 1) * wide_tiles < 2 * kComputeUnits) {       // too few 256-wide tiles to fill the chip

@@ -37,6 +37,7 @@ struct GemmParams {
     int32_t tall_rows;        // bf16 kernel: a row tile may be up to this many rows higher than BM (0 or 32), see locate_tile
     int32_t chunked;          // tile numbering: groups dealt to the XCDs in chunks of about this many tiles (0: single groups), see locate_tile
     int32_t tall_first;       // bf16 kernel: tile numbering with the tall tiles of a chunk of groups first, see locate_tile
+    int32_t balance;          // 1: no XCD runs more than an eighth of the launch's tiles, see stolen_tile
 };
 
 struct TileCoord {
@@ -76,17 +77,41 @@ __device__ __forceinline__ TileCoord locate_tile(const GemmParams& p) {
         cnt = p.offsets[e_l + 1] - seg0;
     }
     const int stride = p.xcd_remap ? 8 : 1;
-    const int x = p.xcd_remap ? (int)(blockIdx.x & 7) : 0;           // my chunks: those whose number is x modulo stride
-    const int idx = p.xcd_remap ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;    // my position among their tiles
+    int x = p.xcd_remap ? (int)(blockIdx.x & 7) : 0;                 // my chunks: those whose number is x modulo stride
+    int idx = p.xcd_remap ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;          // my position among their tiles
+    // (both change below when the block takes a tile of another XCD)
     // my lane's expert: its row tiles, its chunks, and what my XCD gets of each of its row blocks
     const RowTiles rt_l = row_tiles_of(cnt, BM, p.tall_rows);
     const ChunkPlan c_l = plan_chunks(rt_l.mtiles, cnt <= BM / 2, p.NT, p.chunked);
     const int chunks_l = c_l.nb * c_l.nch;
     const int cb_l = lane_prefix_sum(chunks_l, lane) - chunks_l;    // chunks of the experts before mine
-    int tiles_l = 0;
-    for (int b = 0; b < c_l.nb; ++b) tiles_l += share_of_block(c_l, b, x - cb_l, stride).tiles;
-    const int incl = lane_prefix_sum(tiles_l, lane);
-    if (idx >= __builtin_amdgcn_readlane(incl, 63)) return t;
+    auto share_of = [&](int xx) __attribute__((always_inline)) {     // what XCD xx gets of my lane's expert
+        int n = 0;
+        for (int b = 0; b < c_l.nb; ++b) n += share_of_block(c_l, b, xx - cb_l, stride).tiles;
+        return n;
+    };
+    int tiles_l = share_of(x);
+    int incl = lane_prefix_sum(tiles_l, lane);
+    const int mine = __builtin_amdgcn_readlane(incl, 63);            // tiles of my XCD
+    if (p.balance && stride == 8) {
+        // no XCD runs more than its even share of the launch's tiles (see stolen_tile)
+        const int total = __builtin_amdgcn_readlane(lane_prefix_sum(rt_l.mtiles * p.NT, lane), 63);
+        const int A = (total + 7) >> 3;
+        if (idx >= min(mine, A)) {
+            if (idx >= A || mine >= A) return t;                     // given away, or beyond every tile
+            int T[8];
+#pragma unroll
+            for (int xx = 0; xx < 8; ++xx) T[xx] = __builtin_amdgcn_readlane(lane_prefix_sum(share_of(xx), lane), 63);
+            const StolenTile st = stolen_tile(T, A, x, idx - mine);
+            if (st.idx < 0) return t;
+            x = st.x;
+            idx = st.idx;
+            tiles_l = share_of(x);
+            incl = lane_prefix_sum(tiles_l, lane);
+        }
+    } else if (idx >= mine) {
+        return t;
+    }
     const unsigned long long holds = __ballot(idx < incl);           // lanes of this and later experts
     const int src = __builtin_amdgcn_readfirstlane(__ffsll((long long)holds) - 1);
     const int mtiles = uniform_of(rt_l.mtiles, src), tall = uniform_of(rt_l.tall, src);
@@ -148,6 +173,7 @@ inline void fill_common(GemmParams& p, const moe_shape& s, const Geom& g, const 
     p.half_tiles = get_opt(OPT_HALF_TILES);
     p.tall_rows = (s.dtype == MOE_DTYPE_BF16 && get_opt(OPT_TALL_TILES)) ? 32 : 0;
     p.tall_first = get_opt(OPT_TALL_FIRST);
+    p.balance = get_opt(OPT_BALANCE);
     // chunks only when the experts have more than half a row tile of rows on average: below that the launch streams
     // the weights, single groups spread over the XCDs are the better order, and the grid needs no slack for chunks
     const int64_t rows_each = (int64_t)s.T * s.k / std::max(1, a.e_end - a.e_begin);

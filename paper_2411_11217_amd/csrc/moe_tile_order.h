@@ -128,6 +128,38 @@ MOE_HD TileInExpert tile_in_block(const ChunkPlan& c, int b, const BlockShare& s
     return t;
 }
 
+// Evening out the XCDs.  Dealt in whole chunks, the XCDs' shares T[0..7] of a launch differ by up to a chunk per expert
+// (experts of different heights have chunks of different sizes and numbers), and the launch lasts as long as the
+// largest share.  So no XCD runs more than A = ceil(all tiles / 8) tiles: an XCD with more gives its tiles number
+// A .. T[x] - 1 away, and on an XCD with fewer the blocks number T[x] .. A - 1 take them, in the order of the XCDs on
+// both sides.  -> sequence and tile number that block number T[x] + j of XCD x runs instead (idx < 0: none is left).
+// The tiles given away are the last ones of their XCD's order, so all but a few blocks still run next to their
+// chunk's other tiles.
+struct StolenTile {
+    int x, idx;
+};
+MOE_HD StolenTile stolen_tile(const int* T, int A, int x, int j) {
+    int d = j, surplus = 0;                                           // d: my number among all takers
+    for (int i = 0; i < 8; ++i) {
+        if (i < x && T[i] < A) d += A - T[i];
+        if (T[i] > A) surplus += T[i] - A;
+    }
+    StolenTile t;
+    t.x = 0;
+    t.idx = -1;
+    if (d >= surplus) return t;
+    for (int i = 0; i < 8; ++i) {
+        const int sur = T[i] > A ? T[i] - A : 0;
+        if (d < sur) {
+            t.x = i;
+            t.idx = A + d;
+            return t;
+        }
+        d -= sur;
+    }
+    return t;
+}
+
 // First row and height of row tile mt of a segment of `rows` rows that starts at row seg.
 struct RowSpan {
     int row0, rows_here;

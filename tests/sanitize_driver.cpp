@@ -158,8 +158,9 @@ static void oracle_layer(int dtype, int T, int H, int F, int E, int k, bool with
 
 // The tile order of the expert GEMMs, evaluated the way the kernels do (per expert: row tiles, chunk plan, the share of
 // every XCD; per block: the expert by cumulative tile counts, the row block, the tile): every tile of every expert is
-// taken by exactly one block, the row tiles partition the segments, and no XCD has more tiles than the grid gives it.
-static void tile_order(const std::vector<int>& counts, int NT, int BM, int tall_rows, int chunked, int stride, bool tall_first) {
+// taken by exactly one block (also when the XCDs even out their shares), the row tiles partition the segments, and no XCD
+// has more tiles than the grid gives it.
+static void tile_order(const std::vector<int>& counts, int NT, int BM, int tall_rows, int chunked, int stride, bool tall_first, bool balance = true) {
     using namespace moe;
     const int E = (int)counts.size();
     int R = 0;
@@ -192,17 +193,34 @@ static void tile_order(const std::vector<int>& counts, int NT, int BM, int tall_
     std::vector<std::vector<char>> seen((size_t)E);
     for (int e = 0; e < E; ++e) seen[(size_t)e].assign((size_t)rt[(size_t)e].mtiles * NT, 0);
     size_t taken = 0;
-    for (int x = 0; x < stride; ++x) {
-        std::vector<int> tiles((size_t)E, 0);
-        int mine = 0;
-        for (int e = 0; e < E; ++e) {
-            for (int b = 0; b < plan[(size_t)e].nb; ++b) tiles[(size_t)e] += share_of_block(plan[(size_t)e], b, x - cb[(size_t)e], stride).tiles;
-            mine += tiles[(size_t)e];
-        }
-        CHECK(mine <= (stride == 8 ? grid / 8 : grid));                   // the grid reaches every tile of this XCD
-        int last_e = -1, last_chunk_nt = -1;
-        (void)last_e; (void)last_chunk_nt;
-        for (int idx = 0; idx < mine; ++idx) {
+    // what every XCD was dealt, and - with the balancing - the even share A that none exceeds
+    auto share = [&](int x, int e) {
+        int n = 0;
+        for (int b = 0; b < plan[(size_t)e].nb; ++b) n += share_of_block(plan[(size_t)e], b, x - cb[(size_t)e], stride).tiles;
+        return n;
+    };
+    int T[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int x = 0; x < stride; ++x)
+        for (int e = 0; e < E; ++e) T[x] += share(x, e);
+    const int A = (int)((total + 7) / 8);
+    for (int xb = 0; xb < stride; ++xb) {
+        CHECK(T[xb] <= (stride == 8 ? grid / 8 : grid));                  // the grid reaches every tile of this XCD
+        // the blocks of XCD xb in their order; with the balancing those beyond min(T, A) take tiles of other XCDs or leave
+        const int blocks = balance && stride == 8 ? std::max(T[xb], A) : T[xb];
+        int ran = 0;
+        for (int blk = 0; blk < blocks; ++blk) {
+            int x = xb, idx = blk;
+            if (balance && stride == 8 && blk >= std::min(T[xb], A)) {
+                if (blk >= A || T[xb] >= A) continue;                      // given away, or beyond every tile
+                const StolenTile st = stolen_tile(T, A, xb, blk - T[xb]);
+                if (st.idx < 0) continue;
+                CHECK(st.x != xb && T[st.x] > A && st.idx >= A && st.idx < T[st.x]);
+                x = st.x;
+                idx = st.idx;
+            }
+            ++ran;
+            std::vector<int> tiles((size_t)E, 0);
+            for (int e = 0; e < E; ++e) tiles[(size_t)e] = share(x, e);
             int e = 0, before = 0;
             while (idx >= before + tiles[(size_t)e]) before += tiles[(size_t)e++];
             const ChunkPlan& c = plan[(size_t)e];
@@ -221,6 +239,7 @@ static void tile_order(const std::vector<int>& counts, int NT, int BM, int tall_
             flag = 1;
             ++taken;
         }
+        if (balance && stride == 8) CHECK(ran <= A);                      // no XCD runs more than the even share
     }
     CHECK(taken == total);
 }
@@ -239,7 +258,7 @@ static void tile_orders() {
                             const int kind = pick(g_rng);
                             c = kind == 0 ? 0 : kind < 6 ? small(g_rng) : kind < 9 ? 256 * (1 + (int)(g_rng() % 40)) + (int)(g_rng() % 64) : large(g_rng);
                         }
-                        tile_order(counts, NT, 256, tall_rows, chunked, stride, rep % 2 == 0);
+                        tile_order(counts, NT, 256, tall_rows, chunked, stride, rep % 2 == 0, rep % 3 != 0);
                         ++cases;
                     }
                 }

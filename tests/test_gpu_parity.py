@@ -188,7 +188,8 @@ def test_reduced_cases_stagewise_and_layer(name, down_cols):
 
 @pytest.mark.parametrize("name", ["bf16_top2_of_4", "bf16_two_experts_ragged", "f32_top2_of_5"])
 @pytest.mark.parametrize("option,default,other", [("xcd_remap", 1, 0), ("fuse_gather", 1, 0), ("half_tiles", 1, 0), ("tall_tiles", 1, 0),
-                                                  ("down_cols", 0, 1), ("down_cols", 0, 2)])
+                                                  ("down_cols", 0, 1), ("down_cols", 0, 2), ("chunked", 32, 0), ("chunked", 32, 8),
+                                                  ("tall_first", 1, 0), ("balance", 1, 0)])
 def test_kernel_options_give_identical_bits(option, default, other, name):
     # which block computes which tile, the tile variant, and who gathers the rows of x do not change any arithmetic
     case = Case(MED[name])
