@@ -87,7 +87,7 @@ MEASURED = [
     (hrm.MIXTRAL_8X7B, 1024, 1024, 1.0, False, 0.735),       # at the ridge: 1.31 x (one row tile per expert, both bounds bite)
     (hrm.MIXTRAL_8X7B, 2048, 2048, 1.0, False, 1.159),
     (hrm.MIXTRAL_8X7B, 4096, 4096, 1.0, False, 2.107),       # compute bound: 0.94 x (the ragged layer beats the dense probe's rate)
-    (hrm.MIXTRAL_8X22B, 8192, 8192, 1.0, False, 7.351),
+    (hrm.MIXTRAL_8X22B, 8192, 8192, 1.0, False, 7.17),
     (hrm.DBRX, 16384, 4096, 0.0, True, 115.3),               # link bound
     (hrm.DBRX, 16384, 4096, 48 / 95, True, 59.0),
     (hrm.DBRX, 16384, 4096, 76 / 95, True, 26.1),            # next to the turning point: link time = 1.27 x GPU time
