@@ -344,6 +344,8 @@ int moe_pre_attention(const moe_linear_shape* qkv_proj, const float* hidden, con
  *   "half_tiles"  1: bf16 row tiles with at most 128 rows run shorter loops.   default 1
  *   "down_cols"   column tiles of the bf16 down GEMM: 0 = by grid size, 1 = 128 wide,
  *                 2 = 256 wide.                                              default 0
+ *   "gate_cols"   column tiles of the bf16 gate/up GEMM: 0 = by grid size, 1 = 64 features wide,
+ *                 2 = 128 features wide.                                     default 0
  *   "tall_tiles"  1: bf16: row tiles may be up to 32 rows higher than 256, so that a small
  *                 remainder of an expert's rows needs no tile of its own.        default 1
  *   "fuse_gather" 1: moe_layer's bf16 gate/up GEMM gathers the rows of x itself (no

@@ -23,8 +23,9 @@ static int g_opts[OPT_COUNT] = {
     /*OPT_TALL_FIRST*/ 1,    // 1: bf16 tile numbering: inside a chunk of column-tile groups the tall row tiles come first
     /*OPT_CHUNKED*/ 32,      // tile numbering: the column-tile groups of an expert go to the XCDs in chunks of about this many tiles (at most 32; 0: single groups)
     /*OPT_BALANCE*/ 1,       // 1: an XCD with more than an eighth of a launch's tiles gives the rest to XCDs with fewer
+    /*OPT_GATE_COLS*/ 0,     // column tiles of the bf16 gate/up GEMM: 0 = by grid size, 1 = 64 features wide, 2 = 128 features wide
 };
-static const char* g_opt_names[OPT_COUNT] = {"xcd_remap", "profile", "down_cols", "half_tiles", "fuse_gather", "tall_tiles", "tall_first", "chunked", "balance"};
+static const char* g_opt_names[OPT_COUNT] = {"xcd_remap", "profile", "down_cols", "half_tiles", "fuse_gather", "tall_tiles", "tall_first", "chunked", "balance", "gate_cols"};
 int get_opt(int id) { return g_opts[id]; }
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

@@ -253,7 +253,11 @@ __device__ __forceinline__ void static_for(F&& f) {
 template <int MODE, int NB>
 __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     constexpr int S = kStages;
-    static_assert(NB == 2 || (NB == 1 && MODE == 1), "gate/up needs the W1 and the W3 tile");
+    // GU1: the gate/up block with half the columns: 64 features, i.e. the 64 rows of the W1 tile and of the W3 tile that
+    // belong to them (rows sel*64 .. of both page tiles; a page tile's LDS image is linear in its rows, so half of it is
+    // one 4 KiB piece).  In LDS the stage looks like the one page tile of the narrow down block: rows 0..63 gate, 64..127 up.
+    constexpr bool GU1 = MODE == 0 && NB == 1;
+    constexpr bool TWO_WALKS = NB == 2 || GU1;   // two page tiles are walked along k
     constexpr int NJ = 4 * NB;                   // 16-column MFMA tiles (B fragments) per wavefront
     constexpr int NMF = 4 * NJ;                  // MFMAs of a group: four 16-row tiles x NJ
     constexpr int kLoadsPerStage = 4 + 2 * NB;   // global_load_lds instructions per wavefront per stage
@@ -286,8 +290,9 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
 
     // ---- weight tiles through the page table -------------------------------------
     const int32_t* trow = p.table + (size_t)(p.table_row_mod ? e % p.table_row_mod : e) * p.ppe + p.group_base;
-    const int pt0 = nt * NB;
+    const int pt0 = GU1 ? (nt >> 1) * 2 : nt * NB;
     const int pt1 = (pt0 + 1 < p.n_page_tiles) ? pt0 + 1 : pt0;   // odd tile count: the second half is masked (NB = 2)
+    const int sel = GU1 ? (nt & 1) : 0;                           // GU1: which half of the two page tiles' rows
     int bad = 0;
     auto page_addr = [&](int page) __attribute__((always_inline)) -> const char* {
         int slot = __builtin_amdgcn_readfirstlane(trow[page]);
@@ -317,16 +322,16 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     auto walk_next_both = [&]() __attribute__((always_inline)) {
         w0.tile += 16384;
         ++w0.within;
-        if (NB == 2) {
+        if (TWO_WALKS) {
             w1.tile += 16384;
             ++w1.within;
         }
-        if (__builtin_expect((w0.within == p.tpp) | (NB == 2 && w1.within == p.tpp), 0)) {
+        if (__builtin_expect((w0.within == p.tpp) | (TWO_WALKS && w1.within == p.tpp), 0)) {
             if (w0.within == p.tpp) {
                 w0.within = 0;
                 w0.tile = page_addr(++w0.page);
             }
-            if (NB == 2 && w1.within == p.tpp) {
+            if (TWO_WALKS && w1.within == p.tpp) {
                 w1.within = 0;
                 w1.tile = page_addr(++w1.page);
             }
@@ -363,11 +368,12 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     // unconditional sequence per half-step under the single test of `extra`; what varies with the number of extra
     // rows is decided inside the asm statement (mfma_extra_tile_8 / _4).
     const int extra = rows_here > BM ? rows_here - BM : 0;
+    // (The 64-feature gate/up block does not split: the halves of its four column fragments are not gate/up pairs.)
     // At most 16 extra rows: ONE extra 16-row MFMA tile, rows BM .. BM + 15, and the two wavefront rows - which hold the
     // same column fragments - take half of the column fragments each (half the extra MFMAs per wavefront).  extra_which:
     // 0 = every fragment (more than 16 extra rows: wavefront row wm has the rows BM + 16 wm ..), 1 / 2 = this
     // wavefront row's half.
-    const bool split_extra = extra > 0 && extra <= 16;
+    const bool split_extra = !GU1 && extra > 0 && extra <= 16;
     const int extra_which = __builtin_amdgcn_readfirstlane(split_extra ? 1 + wm : 0);
     const char* ae_ptr = p.A;
     i32x4 AE[4];
@@ -394,7 +400,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
 #pragma unroll
     for (int o = 0; o < 2; ++o)
 #pragma unroll
-        for (int h = 0; h < 2; ++h) b_voff[o][h] = o * kHalfTile + h * (kWaves * 1024) + b_off;
+        for (int h = 0; h < 2; ++h) b_voff[o][h] = o * kHalfTile + (GU1 ? sel : h) * (kWaves * 1024) + b_off;     // GU1: both loads read piece `sel` of their tile
     auto advance_a = [&](int ia) __attribute__((always_inline)) {
         if (ia == 7) {
             a_ptr += kARowB;
@@ -413,9 +419,9 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     };
     auto load_b = [&](int slot, int kn, int odd, int i) __attribute__((always_inline)) {     // odd = kn & 1, known at compile time by the callers
         char* st = smem + slot * kStageB;
-        const TileWalk& w = i < 2 ? w0 : w1;
-        const int part = (i & 1) * (kWaves * 1024);                       // first or second 4 KiB of the half-tile
-        const char* b = w.tile + odd * kHalfTile + part;
+        const TileWalk& w = (GU1 ? i < 1 : i < 2) ? w0 : w1;
+        const int part = (i & 1) * (kWaves * 1024);                       // first or second 4 KiB of the half-tile in LDS
+        const char* b = w.tile + odd * kHalfTile + (GU1 ? sel * (kWaves * 1024) : part);
         __builtin_amdgcn_global_load_lds((gptr_t)(b + b_off), (lptr_t)(st + (i >= 2 ? kHalfTile : 0) + part + wave * 1024), 16, 0, 0);
         advance_b(kn, odd, i);
     };
@@ -429,11 +435,13 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
     // activations (128-byte rows, two half-steps per stage): chunk 4*hp + lane/16 in half-step parity hp.
     const int b_frag0 = (lane & 15) * kRowB + (((lane >> 4) ^ ((lane >> 2) & 2)) << 4);
     // B fragment j: MODE 0: gate rows wn*64 + (j%4)*16 of tile 0 (j < 4), the same up rows of tile 1 (j >= 4);
+    //               GU1:    gate rows wn*32 + (j%2)*16 of the stage's rows 0..63 (j < 2), the same up rows of its rows 64..127;
     //               MODE 1: rows wn*(16*NJ) + j*16 of the 128*NB rows of the block's tiles
     int b_base[NJ];
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
-        b_base[j] = ((MODE == 0) ? (j >> 2) * 128 + wn * 64 + (j & 3) * 16 : wn * (16 * NJ) + j * 16) * kRowB;
+        b_base[j] = (GU1 ? (j >> 1) * 64 + wn * 32 + (j & 1) * 16
+                         : (MODE == 0) ? (j >> 2) * 128 + wn * 64 + (j & 3) * 16 : wn * (16 * NJ) + j * 16) * kRowB;
 
     // operand registers: two sets of four activation fragments, two sets of weight fragments
     i32x4 AX[4], AY[4], BF[2][NJ];
@@ -458,7 +466,7 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         constexpr int SLOT = decltype(slot_c)::value, I = decltype(l_c)::value;
         constexpr int odd = SLOT & 1;               // S is even: the parity of the half-step is that of its slot
         mfma_16x16x32_then_load<(decltype(i_c)::value * NJ + decltype(j_c)::value) * 4, SLOT * kStageB + (I >= 2 ? kHalfTile : 0) + (I & 1) * (kWaves * 1024)>(
-            a, b, (I < 2 ? w0 : w1).tile, b_voff[odd][I & 1], lds_wave);
+            a, b, ((GU1 ? I < 1 : I < 2) ? w0 : w1).tile, b_voff[odd][I & 1], lds_wave);
         advance_b(kn, odd, I);
     };
 
@@ -710,7 +718,8 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
         });
     };
     if (MODE == 0) {
-        __bf16* h = (__bf16*)p.out + (int64_t)row0 * p.ldo + nt * 128 + wn * 64 + col_l;
+        constexpr int NP = NJ / 2;             // gate/up pairs of a wavefront: fragments j and j + NP
+        __bf16* h = (__bf16*)p.out + (int64_t)row0 * p.ldo + nt * (32 * NP) + wn * (16 * NP) + col_l;
         auto store_rows = [&](auto full, auto n_c) __attribute__((always_inline)) {
             for_row_tiles(n_c, [&](int i, float (&v)[NJ][4]) __attribute__((always_inline)) {
 #pragma unroll
@@ -718,8 +727,8 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                     const int row = a_row_base + i * 16 + r;
                     if (decltype(full)::value || row < rows_here) {
 #pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            h[(int64_t)row * p.ldo + j * 16] = (__bf16)silu_mul(v[j][r], v[j + 4][r]);
+                        for (int j = 0; j < NP; ++j)
+                            h[(int64_t)row * p.ldo + j * 16] = (__bf16)silu_mul(v[j][r], v[j + NP][r]);
                     }
                 }
             });
@@ -735,9 +744,9 @@ __global__ __launch_bounds__(kThreads) void ffn_gemm_bf16(const GemmParams p) {
                 const int row = BM + (split_extra ? 0 : wm * 16) + (lane >> 4) * 4 + r;
                 if (row < rows_here) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
+                    for (int j = 0; j < NP; ++j)
                         if (!split_extra || (j >> 1) == wm)          // split: this wavefront row's gate fragments only
-                            h[(int64_t)row * p.ldo + j * 16] = (__bf16)silu_mul(accE[j][r], accE[j + 4][r]);
+                            h[(int64_t)row * p.ldo + j * 16] = (__bf16)silu_mul(accE[j][r], accE[j + NP][r]);
                 }
             }
         }
@@ -816,7 +825,22 @@ int launch_expert_ffn_bf16(const moe_shape& s, const Geom& g, const FfnArgs& a, 
     GemmParams p{};
     fill_common(p, s, g, a);
     fill_gate_up(p, s, g, a);
-    int rc = launch_stages<0, 2>(p, gemm_grid(p.NT, R, BM, n_exp, p.chunked), st);
+    const int64_t rows_each = R / s.E;
+    const int64_t row_tiles_each = std::max<int64_t>(1, (rows_each - p.tall_rows + BM - 1) / BM);
+    // Gate/up with at most 64 rows per expert on average (the launch streams the weights once): 64-feature column tiles,
+    // twice as many blocks of half the work.  Measured on the Mixtral-8x7B shape, narrow against wide, ms for the layer: 32
+    // tokens 0.502 / 0.505, 128: 0.506 / 0.514, 256: 0.519 / 0.526, 384: 0.551 / 0.549, 512: 0.623 / 0.592, 1024: 0.83 / 0.77
+    // (with more rows a block of half the columns loads the activation rows for half the MFMAs).
+    // gate_cols: 0 = this rule, 1 / 2 = force narrow / wide.
+    const int gopt = get_opt(OPT_GATE_COLS);
+    const bool narrow_gu = gopt == 1 || (gopt == 0 && rows_each <= 64 && n_exp * row_tiles_each * p.NT < 4 * kComputeUnits);
+    int rc;
+    if (narrow_gu) {
+        p.NT = (int32_t)(2 * g.ft);
+        rc = launch_stages<0, 1>(p, gemm_grid(p.NT, R, BM, n_exp, p.chunked), st);
+    } else {
+        rc = launch_stages<0, 2>(p, gemm_grid(p.NT, R, BM, n_exp, p.chunked), st);
+    }
     if (rc != MOE_OK) return rc;
     if (a.mid_event) MOE_HIP_TRY(hipEventRecord(a.mid_event, st));
     fill_down(p, s, g, a);
@@ -827,8 +851,6 @@ int launch_expert_ffn_bf16(const moe_shape& s, const Geom& g, const FfnArgs& a, 
     // ms, 1024 tokens 0.26 / 0.32, 1280 tokens 0.45 / 0.38, 2048 tokens 0.48 / 0.38.
     // down_cols: 0 = this rule, 1 / 2 = force NB.
     const int opt = get_opt(OPT_DOWN_COLS);
-    const int64_t rows_each = R / s.E;
-    const int64_t row_tiles_each = std::max<int64_t>(1, (rows_each - p.tall_rows + BM - 1) / BM);
     const bool narrow = opt == 1 || (opt == 0 && n_exp * row_tiles_each * p.NT < kComputeUnits);
     if (narrow) {
         p.NT = (int32_t)g.dt;

@@ -27,7 +27,7 @@ void set_hip_error(hipError_t e);
     } while (0)
 
 int get_opt(int id);
-enum Opt { OPT_XCD_REMAP = 0, OPT_PROFILE, OPT_DOWN_COLS, OPT_HALF_TILES, OPT_FUSE_GATHER, OPT_TALL_TILES, OPT_TALL_FIRST, OPT_CHUNKED, OPT_BALANCE, OPT_COUNT };
+enum Opt { OPT_XCD_REMAP = 0, OPT_PROFILE, OPT_DOWN_COLS, OPT_HALF_TILES, OPT_FUSE_GATHER, OPT_TALL_TILES, OPT_TALL_FIRST, OPT_CHUNKED, OPT_BALANCE, OPT_GATE_COLS, OPT_COUNT };
 
 // ---- kernel launchers (each returns MOE_OK or MOE_ERR_HIP) -----------------
 int launch_route(const moe_shape& s, const void* x, const void* Wr, const float* bias,

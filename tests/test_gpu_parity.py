@@ -97,6 +97,7 @@ def run_layer(case: Case, ref=None):
 
 @pytest.mark.parametrize("down_cols", [0, 1, 2])
 def test_expert_ffn_row_counts_across_the_tile_variants(down_cols):
+    # (the gate/up launch takes the same choice of column tiles as the down launch: by grid size, narrow, wide)
     """Segments of 1 .. 300 rows, one per expert, on both sides of every threshold of the bf16 kernel's row-tile
     variants (32, 64, 128, 192 rows, the 256-row tile boundary, tiles that take a remainder of up to 32 rows along) and an
     empty one, against the oracle row by row; with the tall tiles switched off every bit stays the same."""
@@ -110,20 +111,24 @@ def test_expert_ffn_row_counts_across_the_tile_variants(down_cols):
     x_bits = v["x"]                                     # [T, H] in the oracle's storage form; k = 1: rows are tokens
     h_ref, o_ref = oracle.expert_ffn(x_bits, offsets, v["W1"], v["W3"], v["W2"], cfg.dtype_code)
     M.set_option("down_cols", down_cols)
+    M.set_option("gate_cols", down_cols)
     try:
         status = torch.zeros(4, dtype=torch.int32, device="cuda")
         h, out = M.moe_expert_ffn(case.shape, case.x, _dev_i32(offsets), case.pw.table_dev, case.pw.pages_dev, status=status)
         torch.cuda.synchronize()
     finally:
         M.set_option("down_cols", 0)
+        M.set_option("gate_cols", 0)
     assert_status_clean(status.cpu().tolist())
     M.set_option("down_cols", down_cols)
+    M.set_option("gate_cols", down_cols)
     M.set_option("tall_tiles", 0)
     try:
         h0, out0 = M.moe_expert_ffn(case.shape, case.x, _dev_i32(offsets), case.pw.table_dev, case.pw.pages_dev, status=status)
         torch.cuda.synchronize()
     finally:
         M.set_option("down_cols", 0)
+        M.set_option("gate_cols", 0)
         M.set_option("tall_tiles", 1)
     assert torch.equal(h0, h) and torch.equal(out0, out)
     for e, c in enumerate(counts):
@@ -189,7 +194,7 @@ def test_reduced_cases_stagewise_and_layer(name, down_cols):
 @pytest.mark.parametrize("name", ["bf16_top2_of_4", "bf16_two_experts_ragged", "f32_top2_of_5"])
 @pytest.mark.parametrize("option,default,other", [("xcd_remap", 1, 0), ("fuse_gather", 1, 0), ("half_tiles", 1, 0), ("tall_tiles", 1, 0),
                                                   ("down_cols", 0, 1), ("down_cols", 0, 2), ("chunked", 32, 0), ("chunked", 32, 8),
-                                                  ("tall_first", 1, 0), ("balance", 1, 0)])
+                                                  ("tall_first", 1, 0), ("balance", 1, 0), ("gate_cols", 0, 1), ("gate_cols", 0, 2)])
 def test_kernel_options_give_identical_bits(option, default, other, name):
     # which block computes which tile, the tile variant, and who gathers the rows of x do not change any arithmetic
     case = Case(MED[name])
