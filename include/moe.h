@@ -2,7 +2,7 @@
  * moe.h -- C ABI of the MI355X (gfx950) MoE-layer library.
  *
  * One call of the layer is what the paper's pipeline runs once per micro-batch
- * inside its post-attention task (section 4.1: "O projection and MoE FFN"):
+ * inside its post-attention task (section 4.1: the O projection, then the MoE FFN):
  * a gating function picks k of the n_e expert feed-forward networks for every
  * token and only those run (section 2.1).  Shape symbols follow the paper's
  * notation table (section 4.2): h1 (here H) model hidden size, h2 (F) expert
