@@ -73,6 +73,15 @@ def main():
                     help="instead of the headline step, time moe_layer on --config's layer shape (weights resident) for "
                          "micro-batch sizes 32 .. 4096: the memory-bound plateau of the decode stage (the paper's section "
                          "6.2 sweeps 32 .. 256) and the turn to compute bound beyond it")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="instead of the layer, time the vendor GEMM library (torch.matmul, bf16) and this library's paged linear "
+                         "map on three dense shapes, same box, same data, same warm state")
+    ap.add_argument("--splits", action="store_true",
+                    help="instead of the layer, time the two expert GEMMs (moe_expert_ffn) of the workload's shape for several ways "
+                         "of splitting its rows over the experts: what raggedness costs")
+    ap.add_argument("--sample-power", action="store_true",
+                    help="after the timed steps run the step for a few seconds more while `amd-smi metric --power --clock --json` is "
+                         "polled beside it; board power and the XCDs' clocks go into the JSON line")
     ap.add_argument("--mu-list", default="", help="--mu-sweep: comma-separated micro-batch sizes instead of the default 32 .. 4096")
     ap.add_argument("--rate-probes", action="store_true",
                     help="instead of the layer, measure the three rates the roofline model takes as its inputs, each with a "
@@ -111,6 +120,8 @@ def main():
         return
     if args.rate_probes:
         return rate_probes(args, M)
+    if args.vendor_gemm:
+        return vendor_gemm_bench(args, M)
     cfg = CONFIGS[args.config]
     for o in args.option:
         name, val = o.split("=")
@@ -123,6 +134,8 @@ def main():
         return prefill_bench(args, cfg, M, make_inputs)
     if args.mu_sweep:
         return mu_sweep_bench(args, cfg, M, make_inputs)
+    if args.splits:
+        return splits_bench(args, cfg, M, make_inputs)
     s = M.make_shape(cfg.T, cfg.H, cfg.F, cfg.E, cfg.k, cfg.dtype, cfg.page_bytes)
     t0 = time.time()
     inp = make_inputs(cfg, threads=16)
@@ -264,12 +277,131 @@ def main():
                               "host_pages": "random order, one copy per page" if args.shuffle_host_pages else "in order, one copy per expert",
                               "note": "every weight page crosses the host link once per step; the step is bound by it"}
     out.update(extra)
+    if args.sample_power:
+        out["power"] = sample_power(step, torch)
     print(json.dumps(out), flush=True)
     if streamer is not None:
         streamer.close()
     if sample_failed:
         print("bench.py: " + sample_failed, file=sys.stderr)
         sys.exit(3)
+
+
+def sample_power(step, torch, seconds=4.0):
+    """Runs `step` back to back for a few seconds while `amd-smi metric --power --clock --json` is polled from a thread:
+    the board's socket power and the clock of every XCD under the workload."""
+    import subprocess
+    import threading
+    watts, clocks, stop = [], [], threading.Event()
+
+    def poll():
+        while not stop.is_set():
+            try:
+                r = subprocess.run(["amd-smi", "metric", "--power", "--clock", "--json"], capture_output=True, text=True, timeout=10)
+                g = json.loads(r.stdout)["gpu_data"][0]
+                watts.append(float(g["power"]["socket_power"]["value"]))
+                clocks.append([float(v["clk"]["value"]) for k, v in sorted(g["clock"].items()) if k.startswith("gfx_")])
+            except Exception:
+                pass
+            time.sleep(0.05)
+
+    for _ in range(20):                                   # reach the steady state first
+        step()
+    torch.cuda.synchronize()
+    th = threading.Thread(target=poll)
+    th.start()
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
+    stop.set()
+    th.join()
+    if not watts:
+        return {"error": "amd-smi gave no reading"}
+    watts.sort()
+    med = lambda v: sorted(v)[len(v) // 2]
+    return {"source": "amd-smi metric --power --clock --json, polled while the step runs back to back", "samples": len(watts),
+            "socket_power_w": {"min": watts[0], "median": med(watts), "max": watts[-1]},
+            "gfx_clk_mhz_median_per_xcd": [med([c[i] for c in clocks if len(c) > i]) for i in range(max(len(c) for c in clocks))]}
+
+
+def vendor_gemm_bench(args, M):
+    """The vendor GEMM library (torch.matmul on bf16 tensors) and this library's paged linear map (the down-projection
+    kernel with one row segment, f32 output) on the same box, the same random data and the same warm state."""
+    import torch
+    torch.manual_seed(0)
+
+    def timed(fn, warm=60, reps=60):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    rows = []
+    # the down projection and the gate/up product of the 4096-token Mixtral-8x7B workload as dense products, and the probe shape
+    for T, N, K in ((8192, 4096, 14336), (8192, 28672, 4096), (2048, 32768, 8192)):
+        a = torch.randn((T, K), device="cuda").to(torch.bfloat16)
+        w = (torch.randn((N, K)) * 0.02).to(torch.bfloat16)
+        wd = w.cuda()
+        ms_v = timed(lambda: a @ wd.T)
+        ls = M.make_linear_shape(T, K, N, 4 << 20)
+        n = M.linear_pages_required(ls)
+        table = torch.arange(n, dtype=torch.int32)
+        pages = torch.empty((n, 4 << 20), dtype=torch.uint8)
+        M.linear_pack(ls, w, table, pages)
+        pd, td = pages.cuda(), table.cuda()
+        ms_l = timed(lambda: M.moe_linear(ls, a, td, pd))
+        flop = 2.0 * T * N * K
+        rows.append({"T": T, "N": N, "K": K, "vendor_ms": round(ms_v, 4), "vendor_tflops": round(flop / ms_v / 1e9, 1),
+                     "library_ms": round(ms_l, 4), "library_tflops": round(flop / ms_l / 1e9, 1)})
+        del a, wd, pd, td
+    print(json.dumps({"metric": "dense bf16 product: vendor GEMM library (bf16 out) against this library's paged linear map (f32 out, "
+                                "allocated per call by the binding)", "unit": "TFLOP/s", "dtype": "bf16", "data": "synthetic", "shapes": rows}), flush=True)
+
+
+def splits_bench(args, cfg, M, make_inputs):
+    """moe_expert_ffn (both expert GEMMs) on the workload's layer shape for several splits of its rows over the experts."""
+    import torch
+    assert cfg.E == 8 and cfg.R == 8192, "the splits are written for 8 experts and 8192 rows"
+    s = M.make_shape(cfg.T, cfg.H, cfg.F, cfg.E, cfg.k, cfg.dtype, cfg.page_bytes)
+    inp = make_inputs(cfg, threads=16)
+    pw = M.PagedWeights(s, inp["W1"], inp["W3"], inp["W2"])
+    pw.to_device(keep_host=False)
+    g = torch.Generator().manual_seed(5)
+    xp = torch.randn((cfg.R, cfg.H), generator=g).to(torch.bfloat16).cuda()
+    rw = torch.rand((cfg.R,), generator=g).cuda()
+    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    splits = {
+        "equal: 8 x 1024": [1024] * 8,
+        "ragged, as the 4096-token workload routes": [1027, 1061, 1029, 995, 1046, 1010, 1014, 1010],
+        "all with 16 rows over a tile multiple": [1040] * 7 + [912],
+        "multiples of 256, uneven": [768, 1280, 1024, 1024, 512, 1536, 1024, 1024],
+    }
+    rows = []
+    for name, cnt in splits.items():
+        assert sum(cnt) == cfg.R
+        off = torch.tensor([0] + list(torch.tensor(cnt).cumsum(0)), dtype=torch.int32).cuda()
+        for _ in range(max(args.warmup, 10)):
+            M.moe_expert_ffn(s, xp, off, pw.table_dev, pw.pages_dev, row_w=rw, status=status)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            M.moe_expert_ffn(s, xp, off, pw.table_dev, pw.pages_dev, row_w=rw, status=status)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        rows.append({"split": name, "rows": cnt, "ms": round(ms, 4), "tflops": round(6.0 * cfg.R * cfg.H * cfg.F / ms / 1e9, 1)})
+    print(json.dumps({"metric": "both expert GEMMs (moe_expert_ffn, outputs allocated per call by the binding) against the split of "
+                                "the rows over the experts", "unit": "ms", "steps": args.steps, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": cfg.name + " (layer shape)"}, "splits": rows}), flush=True)
 
 
 def rate_probes(args, M):
