@@ -290,6 +290,18 @@ def test_all_tokens_to_one_expert_and_empty_experts():
     run_layer(case, ref)
 
 
+def test_expert_with_more_row_tiles_than_the_tile_order_cuts_into_row_blocks():
+    # 70000 of 70400 rows go to one expert: 273 row tiles, beyond the 256 up to which the tile order cuts an expert into row
+    # blocks (it falls back to single column-tile groups there), next to experts with a handful of rows; the XCDs' shares
+    # of such a launch differ, so blocks take tiles of other XCDs
+    cfg = MoEConfig("tallest", "bf16", T=70400, H=128, F=128, E=4, k=1, page_bytes=16384, seed=35, bias=((1, 0.8),))
+    case = Case(cfg)
+    ref = run_stagewise(case)
+    counts = ref["counts"].tolist()
+    assert counts[1] > 256 * 256 and sum(counts) == 70400 and 0 < min(counts) < 2000, counts
+    run_layer(case, ref)
+
+
 def test_identical_experts_and_single_expert_invariants():
     """With identical experts the output does not depend on routing; with one expert the layer is a dense SwiGLU FFN."""
     cfg = MED["bf16_top2_of_4"]
