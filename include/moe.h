@@ -187,7 +187,11 @@ int moe_layer(const moe_shape* s, const void* x, const void* Wr, const float* bi
  * Expert pages live in pinned host memory; the library copies them, expert by
  * expert, into a two-slot device region (2 * pages_per_expert pages: the
  * paper's double buffer of appendix A.1) on `copy_stream` while the expert
- * GEMMs of the previous expert run on `stream`.
+ * GEMMs of the previous expert run on `stream`.  A copy waits only for the GEMMs
+ * that last read the slot it fills - also those of an earlier call on the same
+ * streamer: calls on one streamer must be issued one after the other (from one
+ * host thread or otherwise ordered), and `copy_stream` must be the same stream
+ * in all of them, or the copies of two calls could overtake each other.
  */
 typedef struct moe_streamer moe_streamer;
 

@@ -316,7 +316,7 @@ struct moe_streamer {
     int32_t* slot_table;               // device [2][ppe]
     hipEvent_t loaded[2];              // slot s holds the pages of its current expert
     hipEvent_t released[2];            // the GEMMs reading slot s have been enqueued and finished
-    hipEvent_t ready;                  // x_perm / offsets are ready on the compute stream
+    bool slot_used[2] = {false, false};   // released[s] has been recorded at least once (by this or an earlier call)
 };
 
 extern "C" {
@@ -342,9 +342,9 @@ int moe_stream_create(const moe_shape* s, const void* host_pages, int64_t host_p
     st->host_table.assign(host_page_table, host_page_table + (int64_t)s->E * g.ppe);
     st->slots = (char*)slots;
     st->slot_table = slot_table;
-    // the five events; on a failure those already created are destroyed and the record is freed
-    hipEvent_t* evs[5] = {&st->loaded[0], &st->loaded[1], &st->released[0], &st->released[1], &st->ready};
-    for (int i = 0; i < 5; ++i) {
+    // the four events; on a failure those already created are destroyed and the record is freed
+    hipEvent_t* evs[4] = {&st->loaded[0], &st->loaded[1], &st->released[0], &st->released[1]};
+    for (int i = 0; i < 4; ++i) {
         const hipError_t e = hipEventCreateWithFlags(evs[i], hipEventDisableTiming);
         if (e != hipSuccess) {
             for (int q = 0; q < i; ++q) (void)hipEventDestroy(*evs[q]);
@@ -363,7 +363,6 @@ int moe_stream_destroy(moe_streamer* st) {
         (void)hipEventDestroy(st->loaded[i]);
         (void)hipEventDestroy(st->released[i]);
     }
-    (void)hipEventDestroy(st->ready);
     delete st;
     return MOE_OK;
 }
@@ -394,13 +393,13 @@ static int ffn_streamed(moe_streamer* st, const void* x_perm, const int32_t* gat
                         const float* row_w, void* h_ws, float* out, int32_t* status, hipStream_t comp, hipStream_t copy) {
     const moe_shape& s = st->shape;
     const Geom& g = st->geom;
-    // the copy stream must not overwrite a slot that GEMMs enqueued earlier on the
-    // compute stream (a previous call) may still read
-    MOE_HIP_TRY(hipEventRecord(st->ready, comp));
-    MOE_HIP_TRY(hipStreamWaitEvent(copy, st->ready, 0));
+    // A copy into a slot waits for the GEMMs that last read that slot and for nothing else - also across calls: the first
+    // two copies of a call wait for the last users of their slots in the call before (not for that call's end), so in a
+    // sequence of calls the first expert's pages travel while the last expert's GEMMs, the combine step and the next
+    // call's routing run (the paper's double buffer, appendix A.1, carried over the call boundary).
     for (int e = 0; e < s.E; ++e) {
         const int sl = e & 1;
-        if (e >= 2) MOE_HIP_TRY(hipStreamWaitEvent(copy, st->released[sl], 0));
+        if (st->slot_used[sl]) MOE_HIP_TRY(hipStreamWaitEvent(copy, st->released[sl], 0));
         int rc = enqueue_expert_copy(st, e, copy);
         if (rc != MOE_OK) return rc;
         MOE_HIP_TRY(hipEventRecord(st->loaded[sl], copy));
@@ -410,6 +409,7 @@ static int ffn_streamed(moe_streamer* st, const void* x_perm, const int32_t* gat
         rc = launch_expert_ffn(s, a, comp);
         if (rc != MOE_OK) return rc;
         MOE_HIP_TRY(hipEventRecord(st->released[sl], comp));
+        st->slot_used[sl] = true;
     }
     return MOE_OK;
 }
