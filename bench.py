@@ -82,6 +82,8 @@ def main():
     ap.add_argument("--sample-power", action="store_true",
                     help="after the timed steps run the step for a few seconds more while `amd-smi metric --power --clock --json` is "
                          "polled beside it; board power and the XCDs' clocks go into the JSON line")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="--mu-sweep: also time two micro-batches at a time, each on a stream and a workspace of its own")
     ap.add_argument("--mu-list", default="", help="--mu-sweep: comma-separated micro-batch sizes instead of the default 32 .. 4096")
     ap.add_argument("--rate-probes", action="store_true",
                     help="instead of the layer, measure the three rates the roofline model takes as its inputs, each with a "
@@ -542,6 +544,22 @@ def mu_sweep_bench(args, cfg, M, make_inputs):
                      "weight_tb_per_s": round(weight_bytes / (ms * 1e-3) / 1e12, 2),
                      "tflops": round(6.0 * mu * cfg.k * cfg.H * cfg.F / (ms * 1e-3) / 1e12, 1),
                      "model_ms": round(model["T"] * 1e3, 4)})
+        if args.two_streams:
+            # two micro-batches of the layer at a time, each on a stream and a workspace of its own: the blocks of one fill
+            # the partly filled rounds of the other
+            streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+            ws2, y2 = [ws, M.Workspace(sh)], [y, torch.empty_like(y)]
+            torch.cuda.synchronize()
+
+            def pair(n):
+                for i in range(n):
+                    M.moe_layer(sh, x, Wr, pw.table_dev, pw.pages_dev, workspace=ws2[i & 1], y=y2[i & 1], stream=streams[i & 1])
+            pair(2 * args.warmup)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            pair(2 * args.steps)
+            torch.cuda.synchronize()
+            rows[-1]["ms_per_micro_batch_on_two_streams"] = round((time.perf_counter() - t0) * 1e3 / (2 * args.steps), 4)
     print(json.dumps({"metric": "MoE layer latency against the micro-batch size (weights resident)", "unit": "ms",
                       "steps": args.steps, "warmup": args.warmup, "dtype": cfg.dtype, "data": "synthetic",
                       "config": {"workload": cfg.name + " (layer shape), micro-batch sweep"}, "sweep": rows}), flush=True)
