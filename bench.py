@@ -26,7 +26,7 @@ PEAK_CLOCK_MHZ = 2400.0       # the clock the published peaks are quoted at
 
 # HBM traffic per launch of the gate/up GEMM on the default workload, in bytes, from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/ (None: not measured).
-MEASURED_TRAFFIC = {"c3_mixtral8x7b_t4096": 3.394e9, "c2_mixtral8x7b_t256": 1.948e9, "c4_mixtral8x22b_t8192_skew": 2.112e10}
+MEASURED_TRAFFIC = {"c3_mixtral8x7b_t4096": 3.416e9, "c2_mixtral8x7b_t256": 1.948e9, "c4_mixtral8x22b_t8192_skew": 2.112e10}
 
 
 def cpu_model() -> str:
